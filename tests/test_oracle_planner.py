@@ -1,0 +1,176 @@
+"""Pins of the oracle's split-K planner, append ordering and block manager (no GPU)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+from oracle import planner as op
+from oracle.kv_manager import KVManager
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def load(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+def test_plan_hand_worked_examples():
+    for ex in load("plan_worked_examples.json")["examples"]:
+        p = dict(ex["params"])
+        plan = op.plan_decode(ex["lens"], p.pop("n_kv_heads"), **p)
+        assert plan["chunk"] == ex["chunk"]
+        for key in ("nsplit", "part_off", "item_b", "item_s", "item_blk_begin", "item_blk_end"):
+            assert plan[key].tolist() == ex[key], key
+
+
+def test_plan_named_workload_figures():
+    g = load("plan_worked_examples.json")["named_workloads_seed0"]
+    for cfg in (1, 2, 3, 4):
+        lens, _ = hw.workload_lengths(cfg, 0)
+        plan = op.plan_decode(lens, hw.WORKLOADS[cfg].n_kv_heads, **op.DEFAULTS)
+        assert int(((lens + 15) // 16).sum()) == g[str(cfg)]["W"]
+        assert plan["chunk"] == g[str(cfg)]["chunk"]
+        assert plan["n_items"] == g[str(cfg)]["n_items"]
+        assert int(plan["nsplit"].max()) == g[str(cfg)]["max_nsplit"]
+
+
+def check_plan_invariants(lens, plan, tile_blk, max_split):
+    B = len(lens)
+    nblk = [(int(n) + 15) // 16 for n in lens]
+    assert plan["part_off"][0] == 0 and plan["part_off"][B] == plan["n_items"]
+    cover = {b: [] for b in range(B)}
+    for i in range(plan["n_items"]):
+        b, k = int(plan["item_b"][i]), int(plan["item_s"][i])
+        lo, hi = int(plan["item_blk_begin"][i]), int(plan["item_blk_end"][i])
+        assert 0 <= lo < hi <= nblk[b]
+        assert lo % tile_blk == 0
+        cover[b].append((k, lo, hi))
+    for b in range(B):
+        parts = sorted(cover[b])
+        assert [p[0] for p in parts] == list(range(len(parts)))
+        assert len(parts) == plan["nsplit"][b] <= max_split
+        assert plan["part_off"][b + 1] - plan["part_off"][b] == len(parts)
+        assert parts[0][1] == 0 and parts[-1][2] == nblk[b]
+        for a, c in zip(parts, parts[1:]):
+            assert a[2] == c[1]
+        sizes = [p[2] - p[1] for p in parts]
+        assert all(s == sizes[0] for s in sizes[:-1]) and sizes[-1] <= sizes[0]
+    keys = [(-(int(plan["item_blk_end"][i]) - int(plan["item_blk_begin"][i])), int(plan["item_b"][i]),
+             int(plan["item_s"][i])) for i in range(plan["n_items"])]
+    assert keys == sorted(keys)
+
+
+def test_plan_invariants_random_long_tail():
+    rng = np.random.default_rng(5)
+    for trial in range(300):
+        B = int(rng.integers(1, 40))
+        lens = np.clip(np.rint(np.exp(rng.normal(np.log(2000), 1.5, B))), 1, 131072).astype(int)
+        kw = dict(n_cu=int(rng.integers(1, 300)), wg_per_cu=int(rng.integers(1, 9)),
+                  min_chunk_blk=int(rng.integers(1, 40)), tile_blk=int(rng.choice([1, 2, 4, 8])),
+                  max_split=int(rng.integers(1, 70)))
+        n_kv = int(rng.choice([1, 2, 8]))
+        plan = op.plan_decode(lens, n_kv, **kw)
+        check_plan_invariants(lens, plan, kw["tile_blk"], kw["max_split"])
+        # a trajectory that needs no more than max_split chunks gets no item larger than the chunk
+        for i in range(plan["n_items"]):
+            b = int(plan["item_b"][i])
+            if -(-((int(lens[b]) + 15) // 16) // plan["chunk"]) <= kw["max_split"]:
+                assert plan["item_blk_end"][i] - plan["item_blk_begin"][i] <= plan["chunk"]
+
+
+def test_plan_exhaustive_small():
+    for a in range(1, 70, 3):
+        for b in range(1, 200, 7):
+            lens = [a, b, 200 - b + 1]
+            plan = op.plan_decode(lens, 1, n_cu=2, wg_per_cu=3, min_chunk_blk=1, tile_blk=2, max_split=4)
+            check_plan_invariants(lens, plan, 2, 4)
+
+
+def test_stragglers_are_spread():
+    lens, _ = hw.workload_lengths(4, 0)
+    plan = op.plan_decode(lens, 8, **op.DEFAULTS)
+    sizes = (plan["item_blk_end"] - plan["item_blk_begin"]).astype(int)
+    # the 13 tail trajectories hold most of the blocks but no single item holds more than a chunk
+    assert sizes.max() <= plan["chunk"] < ((lens.max() + 15) // 16) // 4
+    assert (plan["nsplit"][-13:] >= 5).all()
+
+
+def test_append_order_invariants_and_brute_force():
+    rng = np.random.default_rng(3)
+    for trial in range(50):
+        B = int(rng.integers(1, 9))
+        L = rng.integers(0, 5000, B)
+        C = rng.integers(1, 300, B)
+        R = int(rng.choice([16, 32, 64]))
+        plan = op.plan_append(L, C, R)
+        seen = set()
+        for i in range(plan["n_tiles"]):
+            b, r0, n, ext = (int(plan[k][i]) for k in ("tile_b", "tile_row0", "tile_rows_n", "tile_extent"))
+            assert r0 % R == 0 and 1 <= n <= R and r0 + n <= C[b]
+            assert n == R or r0 + n == C[b]
+            assert ext == L[b] + r0 + n
+            seen.add((b, r0))
+        assert len(seen) == plan["n_tiles"] == sum(-(-int(c) // R) for c in C)
+        ext = plan["tile_extent"].astype(int)
+        assert (np.diff(ext) <= 0).all()
+        # ties broken by (b, row0)
+        keys = [(-int(e), int(b), int(r)) for e, b, r in zip(ext, plan["tile_b"], plan["tile_row0"])]
+        assert keys == sorted(keys)
+
+
+def test_append_order_hand_example():
+    plan = op.plan_append([100, 0], [40, 33], 32)
+    # tiles: b0: rows 0-31 (extent 132), rows 32-39 (extent 140); b1: rows 0-31 (32), 32 (33)
+    assert plan["tile_b"].tolist() == [0, 0, 1, 1]
+    assert plan["tile_row0"].tolist() == [32, 0, 32, 0]
+    assert plan["tile_rows_n"].tolist() == [8, 32, 1, 32]
+    assert plan["tile_extent"].tolist() == [140, 132, 33, 32]
+
+
+# ------------------------------------------------------------- block manager
+
+def replay(trace):
+    m = KVManager(trace["n_blocks"])
+    for op_ in trace["ops"]:
+        if op_[0] == "alloc":
+            code, ids = m.alloc(op_[1])
+            assert (code, ids) == (op_[2], op_[3]), op_
+        elif op_[0] == "free":
+            assert m.free(op_[1]) == op_[2], op_
+        else:
+            assert m.num_free() == op_[1], op_
+
+
+def test_manager_hand_written_traces():
+    for tr in load("kv_manager_traces.json")["traces"]:
+        replay(tr)
+
+
+def test_manager_conservation_random():
+    rng = np.random.default_rng(0)
+    m = KVManager(50)
+    held = []
+    for _ in range(2000):
+        if rng.random() < 0.5:
+            n = int(rng.integers(0, 12))
+            before = m.num_free()
+            code, ids = m.alloc(n)
+            if n > before:
+                assert code == -2 and m.num_free() == before
+            else:
+                assert code == 0 and len(set(ids)) == n and not (set(ids) & set(held))
+                held += ids
+        elif held:
+            k = int(rng.integers(1, len(held) + 1))
+            idx = rng.permutation(len(held))[:k]
+            ids = [held[i] for i in idx]
+            assert m.free(ids) == 0
+            held = [h for i, h in enumerate(held) if i not in set(idx.tolist())]
+            # most recently freed comes back first
+            code, got = m.alloc(1)
+            assert got == [ids[-1]]
+            held += got
+        assert m.num_free() + len(held) == 50
