@@ -1,0 +1,202 @@
+/*
+ * heddle.h - C ABI of the trajectory-generation attention path on MI355X (gfx950).
+ *
+ * What it covers.  In agentic RL rollout an LLM agent produces multi-step
+ * trajectories, alternating token generation with tool calls (paper Sec. 2.1);
+ * a trajectory keeps its KV cache while it waits for a tool or is preempted
+ * (Sec. 4.2, "Preemptive Execution"; Algorithm 1), the cache is paged (Sec. 9,
+ * PagedAttention), and a worker runs a batch of trajectories whose lengths are
+ * long-tailed (Sec. 1, Sec. 2.2).  The two GPU operations of that generation
+ * step are exported here:
+ *
+ *   heddle_attn_decode   one new token for every live trajectory of the batch
+ *   heddle_attn_append   a tool-output chunk appended onto the retained cache
+ *                        (the "tool-output prefill" of Sec. 8)
+ *
+ * together with the block manager of the paged pool (heddle_kv_alloc/free) and
+ * the host-side planners whose output the tests compare bit for bit.
+ *
+ * Attention is scaled dot-product attention with grouped query heads:
+ *   out[j] = sum_t softmax_t(scale * q[j] . K[t][j / G]) * V[t][j / G],  G = n_q / n_kv.
+ * bf16 inputs and outputs, fp32 accumulation.
+ *
+ * Memory layout (all device pointers are caller-owned; the library allocates
+ * only its own context, a small pinned staging ring and grow-only scratch):
+ *   kv_pool    bf16 [n_blocks][n_kv_heads][2][16][head_dim]   index 2: 0 = K, 1 = V
+ *   block table in CSR form: token position p of trajectory b is stored in
+ *              block  block_ids[row_off[b] + p / 16], slot p % 16
+ *   q / out    bf16 [rows][n_q_heads][head_dim]
+ *   k / v rows bf16 [rows][n_kv_heads][head_dim]
+ * Slots past a trajectory's length and blocks outside every table may hold
+ * anything (NaN included) and never influence a result.
+ *
+ * Conventions.  Every function returns HEDDLE_OK (0) or a negative code; no
+ * exceptions, no abort, nothing printed.  Arguments are validated before any
+ * device work is enqueued, so a failing call has no device side effect.
+ * Attention calls are asynchronous on the HIP stream passed in and never
+ * synchronise it; host arrays are consumed before the call returns.  A context
+ * is not thread-safe and its attention calls must be issued on one stream at a
+ * time (they share the context's scratch).
+ */
+#ifndef HEDDLE_H
+#define HEDDLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HEDDLE_OK             0
+#define HEDDLE_E_INVAL       (-1)  /* bad argument, bad block id, table too short, ... */
+#define HEDDLE_E_NOMEM       (-2)  /* pool exhausted / caller array too small / malloc failed */
+#define HEDDLE_E_HIP         (-3)  /* a HIP runtime call failed */
+#define HEDDLE_E_UNSUPPORTED (-4)  /* shape outside what the kernels are built for */
+
+#define HEDDLE_BLOCK_TOKENS  16
+#define HEDDLE_MAX_CONTEXT   131072   /* tokens per trajectory */
+
+typedef struct heddle_ctx heddle_ctx;
+
+typedef struct heddle_config {
+  int32_t n_q_heads;      /* multiple of n_kv_heads; group size G = n_q/n_kv in {1,2,4,8} */
+  int32_t n_kv_heads;
+  int32_t head_dim;       /* 64 or 128 */
+  int32_t block_tokens;   /* must be 16 */
+  int32_t n_blocks;       /* pool capacity in blocks (>= 1) */
+  int32_t device;         /* HIP device ordinal; -1 = host-only context: block manager and
+                             planners work, attention calls return HEDDLE_E_UNSUPPORTED */
+  void*   kv_pool;        /* DEVICE, caller-owned, layout above; may be NULL iff device == -1 */
+  /* split-K planner parameters; 0 selects the default in brackets */
+  int32_t n_cu;           /* [compute units of the device; 256 if host-only] */
+  int32_t wg_per_cu;      /* [4]  work items wanted per CU */
+  int32_t min_chunk_blk;  /* [16] smallest split, in blocks */
+  int32_t tile_blk;       /* [4]  splits start at multiples of this many blocks */
+  int32_t max_split;      /* [64] most splits per trajectory */
+  float   scale;          /* 0 selects 1/sqrt(head_dim) */
+} heddle_config;
+
+/* Creates a context.  *out is written only on success.  With device >= 0 the
+ * device is queried and a small pinned staging ring is allocated. */
+int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out);
+/* Synchronises the device if the context has enqueued work, frees everything it owns. */
+int heddle_ctx_destroy(heddle_ctx* ctx);
+
+/* ---- block manager of the paged pool (host only, O(n), all-or-nothing) ----
+ * A trajectory's blocks stay allocated across tool calls and preemption
+ * (Sec. 4.2) and are returned when it finishes.  Stack discipline: a fresh
+ * context hands out 0,1,2,...; free pushes ids in the order given; alloc pops,
+ * most recently freed first.
+ *   alloc: n < 0 -> INVAL; fewer than n free -> NOMEM; nothing changes on error.
+ *   free:  any id out of range, not allocated, or repeated in the call -> INVAL,
+ *          nothing changes. */
+int heddle_kv_alloc(heddle_ctx* ctx, int32_t n, int32_t* out_block_ids /* HOST [n] */);
+int heddle_kv_free(heddle_ctx* ctx, int32_t n, const int32_t* block_ids /* HOST [n] */);
+int heddle_kv_num_free(const heddle_ctx* ctx, int32_t* out);
+
+/* ---- split-K plan for decode (host only) ----------------------------------
+ * Spreads the batch over the GPU: a long-tail trajectory (Sec. 2.2) is cut into
+ * several work items so that no compute unit is left streaming one straggler
+ * alone; items are ordered longest first (the LPT idea of Sec. 4.2).  Rule, all
+ * integer: nblk = ceil(len/16); W = sum nblk; target = max(1, n_cu*wg_per_cu /
+ * n_kv_heads); chunk = max(ceil(W/target), min_chunk_blk) rounded up to a
+ * multiple of tile_blk; per trajectory ns = min(ceil(nblk/chunk), max_split),
+ * per = ceil(nblk/ns) rounded up to tile_blk, nsplit = ceil(nblk/per); split k
+ * covers blocks [k*per, min((k+1)*per, nblk)); partial slot = part_off[b] + k;
+ * items sorted by (-(blk_end-blk_begin), b, k).
+ * All arrays are HOST memory owned by the caller.  cap_items must be at least
+ * the number of items (never more than B*max_split), else NOMEM. */
+typedef struct heddle_plan {
+  int32_t  cap_items;        /* in  */
+  int32_t  n_items;          /* out */
+  int32_t  chunk;            /* out, in blocks */
+  int32_t* item_b;           /* out [n_items] trajectory of the item */
+  int32_t* item_s;           /* out [n_items] split index within the trajectory */
+  int32_t* item_blk_begin;   /* out [n_items] first logical block */
+  int32_t* item_blk_end;     /* out [n_items] one past the last logical block */
+  int32_t* nsplit;           /* out [B] */
+  int32_t* part_off;         /* out [B+1] */
+} heddle_plan;
+int heddle_plan_decode(const heddle_ctx* ctx, int32_t B, const int32_t* len_host, heddle_plan* plan);
+
+/* ---- work order of append (host only) --------------------------------------
+ * One tile per (trajectory, tile_rows consecutive chunk rows); cost of a tile =
+ * number of keys its last row sees = L_b + min(row0 + tile_rows, C_b); tiles are
+ * sorted by (-extent, b, row0).  tile_rows <= 0 selects the kernel's own tile
+ * height for this context.  Arrays are HOST, cap_tiles >= sum ceil(C_b/tile_rows). */
+typedef struct heddle_append_plan {
+  int32_t  cap_tiles;        /* in  */
+  int32_t  n_tiles;          /* out */
+  int32_t  tile_rows;        /* out: the tile height used */
+  int32_t* tile_b;           /* out [n_tiles] */
+  int32_t* tile_row0;        /* out [n_tiles] first chunk row of the tile */
+  int32_t* tile_rows_n;      /* out [n_tiles] rows in the tile (< tile_rows only at a chunk's end) */
+  int32_t* tile_extent;      /* out [n_tiles] */
+} heddle_append_plan;
+int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
+                       const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_plan* plan);
+
+/* ---- decode: one query token per trajectory ---------------------------------
+ * len[b] counts the KV rows the query sees, the new token's own row included.
+ * If k_new/v_new are given, row b is first stored at position len[b]-1 (the
+ * table must cover it); otherwise the caller has stored it already.
+ * Errors: B < 1, len < 1 or > HEDDLE_MAX_CONTEXT, a table row shorter than
+ * ceil(len/16) blocks, NULL required pointer -> INVAL. */
+typedef struct heddle_decode_args {
+  int32_t        B;
+  const int32_t* len_host;       /* HOST   [B] */
+  const int32_t* row_off_host;   /* HOST   [B+1] CSR offsets (validation and planning) */
+  const int32_t* row_off;        /* DEVICE [B+1] same values */
+  const int32_t* block_ids;      /* DEVICE [row_off[B]] physical block of each logical block */
+  const void*    q;              /* DEVICE bf16 [B][n_q][d] */
+  const void*    k_new;          /* DEVICE bf16 [B][n_kv][d] or NULL */
+  const void*    v_new;          /* DEVICE bf16 [B][n_kv][d] or NULL (both or neither) */
+  void*          out;            /* DEVICE bf16 [B][n_q][d] */
+  float*         lse;            /* DEVICE f32  [B][n_q] natural-log sum of exponentials, or NULL */
+} heddle_decode_args;
+int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream);
+
+/* ---- append: a chunk of C_b >= 1 new tokens per trajectory ------------------
+ * The chunk's K/V rows are stored at positions L_b .. L_b+C_b-1 (the table must
+ * already cover L_b + C_b tokens), then chunk row i attends to positions
+ * 0 .. L_b+i: the whole retained context plus the chunk causally, itself
+ * included.  L_b = 0 is legal (first prompt).
+ * Errors: B < 1, C_b < 1, L_b < 0, L_b + C_b > HEDDLE_MAX_CONTEXT, table too
+ * short, NULL pointer -> INVAL. */
+typedef struct heddle_append_args {
+  int32_t        B;
+  const int32_t* ctx_len_host;   /* HOST   [B] L_b */
+  const int32_t* cu_chunk_host;  /* HOST   [B+1] prefix sums of C_b, cu[0] = 0 */
+  const int32_t* row_off_host;   /* HOST   [B+1] */
+  const int32_t* row_off;        /* DEVICE [B+1] */
+  const int32_t* block_ids;      /* DEVICE [row_off[B]] */
+  const void*    q;              /* DEVICE bf16 [sum C][n_q][d] */
+  const void*    k;              /* DEVICE bf16 [sum C][n_kv][d] */
+  const void*    v;              /* DEVICE bf16 [sum C][n_kv][d] */
+  void*          out;            /* DEVICE bf16 [sum C][n_q][d] */
+  float*         lse;            /* DEVICE f32  [sum C][n_q] or NULL */
+} heddle_append_args;
+int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream);
+
+/* ---- measurement aids ---------------------------------------------------------
+ * Average duration in microseconds of the dominant kernel of the last
+ * `heddle_attn_decode` / `heddle_attn_append` calls, measured with HIP events
+ * recorded on the caller's stream around that kernel.  Recording is off by
+ * default; heddle_timing_enable(ctx, 1) clears the statistics and turns it on.
+ * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
+ * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write. */
+int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
+int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
+
+/* Streams `bytes` bytes from `src` (DEVICE) through a plain coalesced read kernel
+ * and writes one checksum word per workgroup to `sink` (DEVICE, >= 4096 uint32);
+ * used to measure the streaming-read ceiling of the device. */
+int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream);
+
+const char* heddle_strerror(int code);
+int heddle_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEDDLE_H */

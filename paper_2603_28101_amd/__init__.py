@@ -1,0 +1,17 @@
+"""MI355X-native paged-KV trajectory attention (decode + tool-chunk append).
+
+Thin ctypes binding over libheddle.so; every step of the path runs in the
+library's HIP kernels.  There is no CPU fallback: if the library is missing the
+import of `paper_2603_28101_amd.binding` raises.
+"""
+from .binding import (  # noqa: F401
+    HeddleError,
+    Context,
+    lib,
+    lib_path,
+    stream_read,
+    E_INVAL,
+    E_NOMEM,
+    E_HIP,
+    E_UNSUPPORTED,
+)

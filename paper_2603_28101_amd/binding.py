@@ -1,0 +1,230 @@
+"""ctypes binding of the C ABI declared in include/heddle.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+OK, E_INVAL, E_NOMEM, E_HIP, E_UNSUPPORTED = 0, -1, -2, -3, -4
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libheddle.so")
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it first (python -m paper_2603_28101_amd.build, or "
+            "__graft_entry__.build()); there is no fallback implementation")
+    return C.CDLL(path)
+
+
+lib = _load()
+
+i32p = C.POINTER(C.c_int32)
+vp = C.c_void_p
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("block_tokens", C.c_int32), ("n_blocks", C.c_int32), ("device", C.c_int32),
+        ("kv_pool", vp),
+        ("n_cu", C.c_int32), ("wg_per_cu", C.c_int32), ("min_chunk_blk", C.c_int32),
+        ("tile_blk", C.c_int32), ("max_split", C.c_int32),
+        ("scale", C.c_float),
+    ]
+
+
+class Plan(C.Structure):
+    _fields_ = [
+        ("cap_items", C.c_int32), ("n_items", C.c_int32), ("chunk", C.c_int32),
+        ("item_b", i32p), ("item_s", i32p), ("item_blk_begin", i32p), ("item_blk_end", i32p),
+        ("nsplit", i32p), ("part_off", i32p),
+    ]
+
+
+class AppendPlan(C.Structure):
+    _fields_ = [
+        ("cap_tiles", C.c_int32), ("n_tiles", C.c_int32), ("tile_rows", C.c_int32),
+        ("tile_b", i32p), ("tile_row0", i32p), ("tile_rows_n", i32p), ("tile_extent", i32p),
+    ]
+
+
+class DecodeArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32),
+        ("len_host", i32p), ("row_off_host", i32p),
+        ("row_off", vp), ("block_ids", vp),
+        ("q", vp), ("k_new", vp), ("v_new", vp), ("out", vp), ("lse", vp),
+    ]
+
+
+class AppendArgs(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32),
+        ("ctx_len_host", i32p), ("cu_chunk_host", i32p), ("row_off_host", i32p),
+        ("row_off", vp), ("block_ids", vp),
+        ("q", vp), ("k", vp), ("v", vp), ("out", vp), ("lse", vp),
+    ]
+
+
+lib.heddle_ctx_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+lib.heddle_ctx_destroy.argtypes = [vp]
+lib.heddle_kv_alloc.argtypes = [vp, C.c_int32, i32p]
+lib.heddle_kv_free.argtypes = [vp, C.c_int32, i32p]
+lib.heddle_kv_num_free.argtypes = [vp, i32p]
+lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
+lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
+lib.heddle_attn_decode.argtypes = [vp, C.POINTER(DecodeArgs), vp]
+lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
+lib.heddle_timing_enable.argtypes = [vp, C.c_int32]
+lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
+lib.heddle_strerror.argtypes = [C.c_int]
+lib.heddle_strerror.restype = C.c_char_p
+for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
+           "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
+           "heddle_attn_append", "heddle_timing_enable", "heddle_timing_read", "heddle_stream_read",
+           "heddle_version"):
+    getattr(lib, _f).restype = C.c_int
+
+
+class HeddleError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib.heddle_strerror(code).decode()} ({code})")
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise HeddleError(code, where)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(i32p)
+
+
+def _dptr(t):
+    """Device pointer of a torch tensor (or a raw integer address / None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("device tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Context:
+    """One paged KV pool with its block manager, planners and attention calls."""
+
+    def __init__(self, n_q_heads, n_kv_heads, head_dim, n_blocks, kv_pool=None, device=-1, *,
+                 n_cu=0, wg_per_cu=0, min_chunk_blk=0, tile_blk=0, max_split=0, scale=0.0):
+        self.cfg = Config(n_q_heads, n_kv_heads, head_dim, 16, n_blocks, device, _dptr(kv_pool),
+                          n_cu, wg_per_cu, min_chunk_blk, tile_blk, max_split, scale)
+        self._pool = kv_pool  # keep the tensor alive
+        self._h = vp()
+        _check(lib.heddle_ctx_create(C.byref(self.cfg), C.byref(self._h)), "heddle_ctx_create")
+        self.max_split = max_split or 64
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, vp()
+            _check(lib.heddle_ctx_destroy(h), "heddle_ctx_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- block manager
+    def kv_alloc(self, n: int) -> np.ndarray:
+        out = np.empty(max(n, 0), dtype=np.int32)
+        _check(lib.heddle_kv_alloc(self._h, n, out.ctypes.data_as(i32p)), "heddle_kv_alloc")
+        return out
+
+    def kv_free(self, ids) -> None:
+        a, p = _i32(ids)
+        _check(lib.heddle_kv_free(self._h, a.shape[0], p), "heddle_kv_free")
+
+    def kv_num_free(self) -> int:
+        n = C.c_int32()
+        _check(lib.heddle_kv_num_free(self._h, C.byref(n)), "heddle_kv_num_free")
+        return n.value
+
+    # ---- planners
+    def plan_decode(self, lens) -> dict:
+        lens_a, lens_p = _i32(lens)
+        B = lens_a.shape[0]
+        cap = max(B * self.max_split, 1)
+        arrs = {k: np.empty(cap, dtype=np.int32) for k in ("item_b", "item_s", "item_blk_begin", "item_blk_end")}
+        nsplit = np.empty(B, dtype=np.int32)
+        part_off = np.empty(B + 1, dtype=np.int32)
+        p = Plan(cap, 0, 0, *(arrs[k].ctypes.data_as(i32p) for k in ("item_b", "item_s", "item_blk_begin", "item_blk_end")),
+                 nsplit.ctypes.data_as(i32p), part_off.ctypes.data_as(i32p))
+        _check(lib.heddle_plan_decode(self._h, B, lens_p, C.byref(p)), "heddle_plan_decode")
+        out = {k: v[: p.n_items].copy() for k, v in arrs.items()}
+        out.update(n_items=p.n_items, chunk=p.chunk, nsplit=nsplit, part_off=part_off)
+        return out
+
+    def plan_append(self, ctx_lens, cu_chunk, tile_rows: int = 0) -> dict:
+        L, Lp = _i32(ctx_lens)
+        cu, cup = _i32(cu_chunk)
+        B = L.shape[0]
+        tr = tile_rows if tile_rows > 0 else 1
+        cap = int(sum(-(-int(cu[b + 1] - cu[b]) // tr) for b in range(B))) if tile_rows > 0 else int(cu[-1])
+        cap = max(cap, 1)
+        arrs = {k: np.empty(cap, dtype=np.int32) for k in ("tile_b", "tile_row0", "tile_rows_n", "tile_extent")}
+        p = AppendPlan(cap, 0, 0, *(arrs[k].ctypes.data_as(i32p) for k in ("tile_b", "tile_row0", "tile_rows_n", "tile_extent")))
+        _check(lib.heddle_plan_append(self._h, B, Lp, cup, tile_rows, C.byref(p)), "heddle_plan_append")
+        out = {k: v[: p.n_tiles].copy() for k, v in arrs.items()}
+        out.update(n_tiles=p.n_tiles, tile_rows=p.tile_rows)
+        return out
+
+    # ---- attention
+    def attn_decode(self, lens, row_off_host, row_off, block_ids, q, out, lse=None, k_new=None,
+                    v_new=None, stream=None) -> None:
+        lens_a, lens_p = _i32(lens)
+        ro_a, ro_p = _i32(row_off_host)
+        args = DecodeArgs(lens_a.shape[0], lens_p, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
+                          _dptr(k_new), _dptr(v_new), _dptr(out), _dptr(lse))
+        _check(lib.heddle_attn_decode(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_decode")
+
+    def attn_append(self, ctx_lens, cu_chunk, row_off_host, row_off, block_ids, q, k, v, out, lse=None,
+                    stream=None) -> None:
+        L, Lp = _i32(ctx_lens)
+        cu, cup = _i32(cu_chunk)
+        ro_a, ro_p = _i32(row_off_host)
+        args = AppendArgs(L.shape[0], Lp, cup, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
+                          _dptr(k), _dptr(v), _dptr(out), _dptr(lse))
+        _check(lib.heddle_attn_append(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_append")
+
+    # ---- measurement
+    def timing_enable(self, on: bool = True) -> None:
+        _check(lib.heddle_timing_enable(self._h, 1 if on else 0), "heddle_timing_enable")
+
+    def timing_read(self, which: int):
+        us, n = C.c_double(), C.c_int64()
+        _check(lib.heddle_timing_read(self._h, which, C.byref(us), C.byref(n)), "heddle_timing_read")
+        return us.value, n.value
+
+
+def stream_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib.heddle_stream_read(_dptr(src), nbytes, _dptr(sink), _stream_ptr(stream)), "heddle_stream_read")

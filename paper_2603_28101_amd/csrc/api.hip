@@ -1,0 +1,475 @@
+// C ABI of libheddle: context, argument validation, plan upload, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <vector>
+
+#include "heddle_internal.h"
+#include "kernels.h"
+
+using namespace heddle;
+
+namespace {
+
+constexpr int kStagingSlots = 8;
+constexpr int kTimedKernels = 4;       // decode, combine, append, kv write
+constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
+
+struct StagingSlot {
+  int32_t* host = nullptr;             // pinned
+  size_t cap_words = 0;
+  hipEvent_t done = nullptr;           // recorded after the H2D copy that reads `host`
+  bool in_flight = false;
+};
+
+struct KernelTimer {
+  std::vector<hipEvent_t> start, stop;
+  int64_t recorded = 0;                // launches recorded since enable
+};
+
+}  // namespace
+
+struct heddle_ctx {
+  heddle_config cfg{};
+  PlanParams plan{};
+  float scale = 0.f;
+  bool has_device = false;
+  bool enqueued = false;
+  std::unique_ptr<BlockManager> blocks;
+
+  StagingSlot staging[kStagingSlots];
+  int next_slot = 0;
+  int32_t* dev_plan = nullptr;
+  size_t dev_plan_words = 0;
+  float* dev_part_acc = nullptr;
+  size_t dev_part_acc_elems = 0;
+  float* dev_part_ml = nullptr;
+  size_t dev_part_ml_elems = 0;
+
+  bool timing_on = false;
+  KernelTimer timers[kTimedKernels];
+
+  // host scratch reused between calls
+  std::vector<DecodeItem> items;
+  std::vector<int32_t> nsplit, part_off;
+  std::vector<AppendTile> tiles;
+};
+
+namespace {
+
+#define HEDDLE_HIP(expr)                         \
+  do {                                           \
+    if ((expr) != hipSuccess) return HEDDLE_E_HIP; \
+  } while (0)
+
+class DeviceGuard {
+ public:
+  explicit DeviceGuard(int dev) {
+    ok_ = hipGetDevice(&prev_) == hipSuccess;
+    if (ok_ && prev_ != dev) ok_ = hipSetDevice(dev) == hipSuccess;
+    switched_ = ok_ && prev_ != dev;
+  }
+  ~DeviceGuard() {
+    if (switched_) (void)hipSetDevice(prev_);
+  }
+  bool ok() const { return ok_; }
+
+ private:
+  int prev_ = 0;
+  bool ok_ = false, switched_ = false;
+};
+
+int grow_device(void** ptr, size_t* have, size_t want, size_t elem_bytes) {
+  if (want <= *have) return HEDDLE_OK;
+  // grow-only scratch: the old buffer may still be read by enqueued work
+  HEDDLE_HIP(hipDeviceSynchronize());
+  if (*ptr != nullptr) HEDDLE_HIP(hipFree(*ptr));
+  *ptr = nullptr;
+  *have = 0;
+  const size_t cap = want + want / 4;
+  void* p = nullptr;
+  if (hipMalloc(&p, cap * elem_bytes) != hipSuccess) return HEDDLE_E_NOMEM;
+  *ptr = p;
+  *have = cap;
+  return HEDDLE_OK;
+}
+
+// Takes the next pinned staging slot, waiting for the copy that last used it.
+int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
+  StagingSlot& s = ctx->staging[ctx->next_slot];
+  ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+  if (s.in_flight) {
+    HEDDLE_HIP(hipEventSynchronize(s.done));
+    s.in_flight = false;
+  }
+  if (words > s.cap_words) {
+    if (s.host != nullptr) HEDDLE_HIP(hipHostFree(s.host));
+    s.host = nullptr;
+    s.cap_words = 0;
+    const size_t cap = words + words / 2 + 1024;
+    void* p = nullptr;
+    if (hipHostMalloc(&p, cap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) return HEDDLE_E_NOMEM;
+    s.host = static_cast<int32_t*>(p);
+    s.cap_words = cap;
+  }
+  *out = &s;
+  return HEDDLE_OK;
+}
+
+int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream) {
+  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, words, sizeof(int32_t));
+  if (rc != HEDDLE_OK) return rc;
+  HEDDLE_HIP(hipMemcpyAsync(ctx->dev_plan, s->host, words * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+  HEDDLE_HIP(hipEventRecord(s->done, stream));
+  s->in_flight = true;
+  return HEDDLE_OK;
+}
+
+struct TimedScope {
+  heddle_ctx* ctx;
+  int which;
+  hipStream_t stream;
+  int idx = -1;
+  TimedScope(heddle_ctx* c, int w, hipStream_t s) : ctx(c), which(w), stream(s) {
+    if (ctx->timing_on) {
+      KernelTimer& t = ctx->timers[which];
+      idx = static_cast<int>(t.recorded % kEventPairs);
+      (void)hipEventRecord(t.start[idx], stream);
+    }
+  }
+  ~TimedScope() {
+    if (idx >= 0) {
+      KernelTimer& t = ctx->timers[which];
+      (void)hipEventRecord(t.stop[idx], stream);
+      ++t.recorded;
+    }
+  }
+};
+
+bool table_covers(const int32_t* row_off_host, int32_t b, int64_t tokens) {
+  const int64_t have = static_cast<int64_t>(row_off_host[b + 1]) - row_off_host[b];
+  return have >= (tokens + HEDDLE_BLOCK_TOKENS - 1) / HEDDLE_BLOCK_TOKENS;
+}
+
+}  // namespace
+
+extern "C" {
+
+int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
+  if (cfg == nullptr || out == nullptr) return HEDDLE_E_INVAL;
+  if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads != 0) return HEDDLE_E_INVAL;
+  if (cfg->block_tokens != HEDDLE_BLOCK_TOKENS || cfg->n_blocks < 1) return HEDDLE_E_INVAL;
+  if (cfg->head_dim < 8 || cfg->head_dim % 8 != 0) return HEDDLE_E_INVAL;
+  if (cfg->n_cu < 0 || cfg->wg_per_cu < 0 || cfg->min_chunk_blk < 0 || cfg->tile_blk < 0 || cfg->max_split < 0)
+    return HEDDLE_E_INVAL;
+  if (cfg->device < -1 || (cfg->device >= 0 && cfg->kv_pool == nullptr)) return HEDDLE_E_INVAL;
+  if (!(cfg->scale >= 0.f) || !std::isfinite(cfg->scale)) return HEDDLE_E_INVAL;
+  if (cfg->device >= 0 && !decode_shape_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim))
+    return HEDDLE_E_UNSUPPORTED;
+
+  std::unique_ptr<heddle_ctx> ctx(new (std::nothrow) heddle_ctx);
+  if (!ctx) return HEDDLE_E_NOMEM;
+  ctx->cfg = *cfg;
+  ctx->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
+  ctx->blocks.reset(new (std::nothrow) BlockManager(cfg->n_blocks));
+  if (!ctx->blocks) return HEDDLE_E_NOMEM;
+
+  int n_cu = cfg->n_cu;
+  if (cfg->device >= 0) {
+    int count = 0;
+    HEDDLE_HIP(hipGetDeviceCount(&count));
+    if (cfg->device >= count) return HEDDLE_E_INVAL;
+    DeviceGuard guard(cfg->device);
+    if (!guard.ok()) return HEDDLE_E_HIP;
+    if (n_cu == 0) HEDDLE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, cfg->device));
+    for (StagingSlot& s : ctx->staging) HEDDLE_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    ctx->has_device = true;
+  } else if (n_cu == 0) {
+    n_cu = 256;
+  }
+  ctx->plan.n_kv_heads = cfg->n_kv_heads;
+  ctx->plan.n_cu = n_cu;
+  ctx->plan.wg_per_cu = cfg->wg_per_cu ? cfg->wg_per_cu : 4;
+  ctx->plan.min_chunk_blk = cfg->min_chunk_blk ? cfg->min_chunk_blk : 16;
+  ctx->plan.tile_blk = cfg->tile_blk ? cfg->tile_blk : 4;
+  ctx->plan.max_split = cfg->max_split ? cfg->max_split : 64;
+  *out = ctx.release();
+  return HEDDLE_OK;
+}
+
+int heddle_ctx_destroy(heddle_ctx* ctx) {
+  if (ctx == nullptr) return HEDDLE_E_INVAL;
+  int rc = HEDDLE_OK;
+  if (ctx->has_device) {
+    DeviceGuard guard(ctx->cfg.device);
+    if (ctx->enqueued && hipDeviceSynchronize() != hipSuccess) rc = HEDDLE_E_HIP;
+    for (StagingSlot& s : ctx->staging) {
+      if (s.host) (void)hipHostFree(s.host);
+      if (s.done) (void)hipEventDestroy(s.done);
+    }
+    if (ctx->dev_plan) (void)hipFree(ctx->dev_plan);
+    if (ctx->dev_part_acc) (void)hipFree(ctx->dev_part_acc);
+    if (ctx->dev_part_ml) (void)hipFree(ctx->dev_part_ml);
+    for (KernelTimer& t : ctx->timers) {
+      for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
+      for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
+    }
+  }
+  delete ctx;
+  return rc;
+}
+
+int heddle_kv_alloc(heddle_ctx* ctx, int32_t n, int32_t* out_block_ids) {
+  if (ctx == nullptr) return HEDDLE_E_INVAL;
+  return ctx->blocks->alloc(n, out_block_ids);
+}
+
+int heddle_kv_free(heddle_ctx* ctx, int32_t n, const int32_t* block_ids) {
+  if (ctx == nullptr) return HEDDLE_E_INVAL;
+  return ctx->blocks->release(n, block_ids);
+}
+
+int heddle_kv_num_free(const heddle_ctx* ctx, int32_t* out) {
+  if (ctx == nullptr || out == nullptr) return HEDDLE_E_INVAL;
+  *out = ctx->blocks->num_free();
+  return HEDDLE_OK;
+}
+
+int heddle_plan_decode(const heddle_ctx* ctx, int32_t B, const int32_t* len_host, heddle_plan* plan) {
+  if (ctx == nullptr || plan == nullptr || len_host == nullptr || B < 1) return HEDDLE_E_INVAL;
+  if (!plan->item_b || !plan->item_s || !plan->item_blk_begin || !plan->item_blk_end || !plan->nsplit ||
+      !plan->part_off)
+    return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b)
+    if (len_host[b] < 1 || len_host[b] > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+  std::vector<DecodeItem> items;
+  std::vector<int32_t> nsplit, part_off;
+  int32_t chunk = 0;
+  plan_decode(ctx->plan, B, len_host, items, nsplit, part_off, chunk);
+  if (static_cast<int64_t>(items.size()) > plan->cap_items) return HEDDLE_E_NOMEM;
+  plan->n_items = static_cast<int32_t>(items.size());
+  plan->chunk = chunk;
+  for (size_t i = 0; i < items.size(); ++i) {
+    plan->item_b[i] = items[i].b;
+    plan->item_s[i] = items[i].s;
+    plan->item_blk_begin[i] = items[i].blk_begin;
+    plan->item_blk_end[i] = items[i].blk_end;
+  }
+  std::memcpy(plan->nsplit, nsplit.data(), sizeof(int32_t) * B);
+  std::memcpy(plan->part_off, part_off.data(), sizeof(int32_t) * (static_cast<size_t>(B) + 1));
+  return HEDDLE_OK;
+}
+
+int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
+                       const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_plan* plan) {
+  if (ctx == nullptr || plan == nullptr || ctx_len_host == nullptr || cu_chunk_host == nullptr || B < 1)
+    return HEDDLE_E_INVAL;
+  if (!plan->tile_b || !plan->tile_row0 || !plan->tile_rows_n || !plan->tile_extent) return HEDDLE_E_INVAL;
+  if (cu_chunk_host[0] != 0) return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t C = static_cast<int64_t>(cu_chunk_host[b + 1]) - cu_chunk_host[b];
+    if (C < 1 || ctx_len_host[b] < 0 || ctx_len_host[b] + C > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+  }
+  if (tile_rows <= 0) tile_rows = 128 / (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads);
+  if (tile_rows < 1) tile_rows = 1;
+  std::vector<AppendTile> tiles;
+  plan_append(B, ctx_len_host, cu_chunk_host, tile_rows, tiles);
+  if (static_cast<int64_t>(tiles.size()) > plan->cap_tiles) return HEDDLE_E_NOMEM;
+  plan->n_tiles = static_cast<int32_t>(tiles.size());
+  plan->tile_rows = tile_rows;
+  for (size_t i = 0; i < tiles.size(); ++i) {
+    plan->tile_b[i] = tiles[i].b;
+    plan->tile_row0[i] = tiles[i].row0;
+    plan->tile_rows_n[i] = tiles[i].rows;
+    plan->tile_extent[i] = tiles[i].extent;
+  }
+  return HEDDLE_OK;
+}
+
+int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+  if (ctx == nullptr || args == nullptr) return HEDDLE_E_INVAL;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  const int32_t B = args->B;
+  if (B < 1 || !args->len_host || !args->row_off_host || !args->row_off || !args->block_ids || !args->q ||
+      !args->out)
+    return HEDDLE_E_INVAL;
+  if ((args->k_new == nullptr) != (args->v_new == nullptr)) return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t n = args->len_host[b];
+    if (n < 1 || n > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+    if (args->row_off_host[b + 1] < args->row_off_host[b] || !table_covers(args->row_off_host, b, n))
+      return HEDDLE_E_INVAL;
+  }
+  if (args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
+
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  int32_t chunk = 0;
+  plan_decode(ctx->plan, B, args->len_host, ctx->items, ctx->nsplit, ctx->part_off, chunk);
+  const size_t n_items = ctx->items.size();
+  const size_t n_parts = static_cast<size_t>(ctx->part_off[B]);
+  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
+
+  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems,
+                       n_parts * Hq * D, sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 2,
+                   sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+
+  // plan image: lens[B] | first_pos[B] | cu_rows[B+1] | part_off[B+1] | nsplit[B] | 4 x items
+  const size_t words = 4 * static_cast<size_t>(B) + 2 + 4 * n_items;
+  StagingSlot* slot = nullptr;
+  rc = acquire_slot(ctx, words, &slot);
+  if (rc != HEDDLE_OK) return rc;
+  int32_t* w = slot->host;
+  int32_t* h_lens = w;
+  int32_t* h_first = h_lens + B;
+  int32_t* h_cu = h_first + B;
+  int32_t* h_part_off = h_cu + B + 1;
+  int32_t* h_nsplit = h_part_off + B + 1;
+  int32_t* h_item_b = h_nsplit + B;
+  int32_t* h_item_s = h_item_b + n_items;
+  int32_t* h_item_lo = h_item_s + n_items;
+  int32_t* h_item_hi = h_item_lo + n_items;
+  for (int32_t b = 0; b < B; ++b) {
+    h_lens[b] = args->len_host[b];
+    h_first[b] = args->len_host[b] - 1;
+    h_cu[b] = b;
+    h_nsplit[b] = ctx->nsplit[b];
+  }
+  h_cu[B] = B;
+  std::memcpy(h_part_off, ctx->part_off.data(), sizeof(int32_t) * (static_cast<size_t>(B) + 1));
+  for (size_t i = 0; i < n_items; ++i) {
+    h_item_b[i] = ctx->items[i].b;
+    h_item_s[i] = ctx->items[i].s;
+    h_item_lo[i] = ctx->items[i].blk_begin;
+    h_item_hi[i] = ctx->items[i].blk_end;
+  }
+  rc = upload(ctx, slot, words, stream);
+  if (rc != HEDDLE_OK) return rc;
+  ctx->enqueued = true;
+  const int32_t* d = ctx->dev_plan;
+
+  if (args->k_new != nullptr) {
+    KvWriteLaunch kw{};
+    kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
+    kw.row_off = args->row_off;
+    kw.block_ids = args->block_ids;
+    kw.first_pos = d + (h_first - w);
+    kw.cu_rows = d + (h_cu - w);
+    kw.k = static_cast<const uint16_t*>(args->k_new);
+    kw.v = static_cast<const uint16_t*>(args->v_new);
+    kw.B = B;
+    kw.n_rows = B;
+    kw.n_kv_heads = ctx->cfg.n_kv_heads;
+    kw.head_dim = D;
+    TimedScope t(ctx, 3, stream);
+    HEDDLE_HIP(launch_kv_write(kw, stream));
+  }
+
+  DecodeLaunch dl{};
+  dl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
+  dl.row_off = args->row_off;
+  dl.block_ids = args->block_ids;
+  dl.lens = d + (h_lens - w);
+  dl.item_b = d + (h_item_b - w);
+  dl.item_s = d + (h_item_s - w);
+  dl.item_blk_begin = d + (h_item_lo - w);
+  dl.item_blk_end = d + (h_item_hi - w);
+  dl.part_off = d + (h_part_off - w);
+  dl.nsplit = d + (h_nsplit - w);
+  dl.q = static_cast<const uint16_t*>(args->q);
+  dl.part_acc = ctx->dev_part_acc;
+  dl.part_ml = ctx->dev_part_ml;
+  dl.out = static_cast<uint16_t*>(args->out);
+  dl.lse = args->lse;
+  dl.B = B;
+  dl.n_items = static_cast<int32_t>(n_items);
+  dl.n_q_heads = Hq;
+  dl.n_kv_heads = ctx->cfg.n_kv_heads;
+  dl.head_dim = D;
+  dl.scale_log2 = ctx->scale * 1.4426950408889634f;
+  {
+    TimedScope t(ctx, 0, stream);
+    HEDDLE_HIP(launch_decode_splitk(dl, stream));
+  }
+  {
+    TimedScope t(ctx, 1, stream);
+    HEDDLE_HIP(launch_decode_combine(dl, stream));
+  }
+  return HEDDLE_OK;
+}
+
+int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream) {
+  (void)hip_stream;
+  if (ctx == nullptr || args == nullptr) return HEDDLE_E_INVAL;
+  return HEDDLE_E_UNSUPPORTED;
+}
+
+int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {
+  if (ctx == nullptr) return HEDDLE_E_INVAL;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  if (on) {
+    HEDDLE_HIP(hipDeviceSynchronize());
+    for (KernelTimer& t : ctx->timers) {
+      while (t.start.size() < static_cast<size_t>(kEventPairs)) {
+        hipEvent_t a = nullptr, b = nullptr;
+        HEDDLE_HIP(hipEventCreate(&a));
+        t.start.push_back(a);
+        HEDDLE_HIP(hipEventCreate(&b));
+        t.stop.push_back(b);
+      }
+      t.recorded = 0;
+    }
+  }
+  ctx->timing_on = on != 0;
+  return HEDDLE_OK;
+}
+
+int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches) {
+  if (ctx == nullptr || which < 0 || which >= kTimedKernels || avg_us == nullptr) return HEDDLE_E_INVAL;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  KernelTimer& t = ctx->timers[which];
+  const int64_t n = t.recorded < kEventPairs ? t.recorded : kEventPairs;
+  double total_ms = 0.0;
+  for (int64_t i = 0; i < n; ++i) {
+    HEDDLE_HIP(hipEventSynchronize(t.stop[i]));
+    float ms = 0.f;
+    HEDDLE_HIP(hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+    total_ms += ms;
+  }
+  *avg_us = n > 0 ? total_ms * 1000.0 / static_cast<double>(n) : 0.0;
+  if (n_launches) *n_launches = n;
+  return HEDDLE_OK;
+}
+
+int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream) {
+  if (src == nullptr || sink == nullptr || bytes < 16) return HEDDLE_E_INVAL;
+  HEDDLE_HIP(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)));
+  return HEDDLE_OK;
+}
+
+const char* heddle_strerror(int code) {
+  switch (code) {
+    case HEDDLE_OK: return "ok";
+    case HEDDLE_E_INVAL: return "invalid argument";
+    case HEDDLE_E_NOMEM: return "out of blocks or memory";
+    case HEDDLE_E_HIP: return "HIP runtime error";
+    case HEDDLE_E_UNSUPPORTED: return "unsupported shape or context";
+    default: return "unknown error";
+  }
+}
+
+int heddle_version(void) { return 1; }
+
+}  // extern "C"

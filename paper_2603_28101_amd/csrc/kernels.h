@@ -1,0 +1,52 @@
+// Launch interface between the host API and the HIP kernels of libheddle.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace heddle {
+
+// Arguments of the split-K decode pass.  All pointers are device memory.
+struct DecodeLaunch {
+  const uint16_t* pool;        // bf16 [n_blocks][n_kv][2][16][d]
+  const int32_t* row_off;      // [B+1]
+  const int32_t* block_ids;    // CSR block table
+  const int32_t* lens;         // [B]
+  const int32_t* item_b;       // [n_items] plan arrays
+  const int32_t* item_s;
+  const int32_t* item_blk_begin;
+  const int32_t* item_blk_end;
+  const int32_t* part_off;     // [B+1]
+  const int32_t* nsplit;       // [B]
+  const uint16_t* q;           // bf16 [B][n_q][d]
+  float* part_acc;             // f32 [n_parts][n_q][d]   unnormalised sum of p * v
+  float* part_ml;              // f32 [n_parts][n_q][2]   (max logit in log2 units, sum of p)
+  uint16_t* out;               // bf16 [B][n_q][d]
+  float* lse;                  // f32 [B][n_q] or nullptr
+  int32_t B, n_items, n_q_heads, n_kv_heads, head_dim;
+  float scale_log2;            // softmax scale times log2(e)
+};
+
+// Returns hipSuccess or the launch error; HEDDLE_E_UNSUPPORTED shapes are rejected by the caller.
+bool decode_shape_supported(int32_t group, int32_t head_dim);
+hipError_t launch_decode_splitk(const DecodeLaunch& a, hipStream_t stream);
+hipError_t launch_decode_combine(const DecodeLaunch& a, hipStream_t stream);
+
+// Scatter of new K/V rows into the paged pool.  Row i (of n_rows) belongs to trajectory
+// row_traj[i] ... expressed through cu_rows: trajectory b owns rows [cu_rows[b], cu_rows[b+1])
+// and its first row goes to token position first_pos[b].
+struct KvWriteLaunch {
+  uint16_t* pool;
+  const int32_t* row_off;
+  const int32_t* block_ids;
+  const int32_t* first_pos;    // [B] device
+  const int32_t* cu_rows;      // [B+1] device
+  const uint16_t* k;           // bf16 [n_rows][n_kv][d]
+  const uint16_t* v;
+  int32_t B, n_rows, n_kv_heads, head_dim;
+};
+hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream);
+
+hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
+
+}  // namespace heddle

@@ -1,0 +1,74 @@
+// Small data-movement kernels: scatter of new K/V rows into the paged pool, and a plain
+// streaming read used to measure what the memory system can deliver.
+#include "kernels.h"
+
+namespace heddle {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// One workgroup per new token row; thread t moves one 16-byte piece of K and of V.
+// Row i of trajectory b (rows cu_rows[b] .. cu_rows[b+1]) goes to position first_pos[b] + i.
+__global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
+  const int row = blockIdx.x;
+  // trajectory of this row: last b with cu_rows[b] <= row
+  int lo = 0, hi = a.B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.cu_rows[mid] <= row) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int pos = a.first_pos[b] + (row - a.cu_rows[b]);
+  const int phys = a.block_ids[a.row_off[b] + pos / 16];
+  const int slot = pos % 16;
+  const int pieces_per_head = a.head_dim / 8;
+  const int n_pieces = a.n_kv_heads * pieces_per_head;
+  for (int t = threadIdx.x; t < n_pieces; t += blockDim.x) {
+    const int h = t / pieces_per_head;
+    const int c = t - h * pieces_per_head;
+    const int64_t src = (static_cast<int64_t>(row) * a.n_kv_heads + h) * a.head_dim + c * 8;
+    const int64_t dst_k = ((static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 + slot) * a.head_dim + c * 8;
+    const int64_t dst_v = dst_k + 16 * a.head_dim;
+    *reinterpret_cast<u32x4*>(a.pool + dst_k) = *reinterpret_cast<const u32x4*>(a.k + src);
+    *reinterpret_cast<u32x4*>(a.pool + dst_v) = *reinterpret_cast<const u32x4*>(a.v + src);
+  }
+}
+
+constexpr int kStreamGroups = 4096;
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, uint64_t n_vec, uint32_t* sink) {
+  uint32_t x = 0;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+    x ^= v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+  }
+  for (; i < n_vec; i += stride) {
+    const u32x4 v = src[i];
+    x ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
+  __shared__ uint32_t s[4];
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+}  // namespace
+
+hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream) {
+  if (a.n_rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_write_kernel, dim3(static_cast<unsigned>(a.n_rows)), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(kStreamGroups), dim3(256), 0, stream,
+                     static_cast<const u32x4*>(src), bytes / 16, sink);
+  return hipGetLastError();
+}
+
+}  // namespace heddle

@@ -1,0 +1,195 @@
+"""Parity of heddle_attn_decode with the float64 oracle, through the C ABI (needs the GPU)."""
+import math
+
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+from oracle import attention as oa
+from oracle import planner as op
+from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64,
+                            bf16_to_host_bits)
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_decode(c, lens=None, pool=None):
+    return oa.decode(c["pool"] if pool is None else pool, c["row_off"], c["block_ids"],
+                     c["lens"] if lens is None else lens, c["q"], c["n_kv_heads"])
+
+
+def small(seed, lens, n_q, n_kv, d, **kw):
+    return hw.build_case(entropy=[0, seed], lens=lens, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=d, threads=4, **kw)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_workload(seed):
+    c = hw.make_workload(1, seed)
+    print("tiny decode seed", seed, "lens", c["lens"].tolist(), flush=True)
+    out, lse = DeviceCase(c).decode()
+    ref, ref_lse = oracle_decode(c)
+    assert_close(out, ref, "tiny out")
+    assert_lse_close(lse, ref_lse, "tiny lse")
+
+
+RAGGED = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 255, 256, 257, 1000, 1024, 2049, 4097]
+
+
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 128), (8, 2, 64), (2, 2, 128), (4, 2, 128), (16, 2, 128),
+                                        (16, 2, 64), (3, 3, 64), (32, 8, 128)])
+def test_ragged_lengths_all_head_shapes(n_q, n_kv, d):
+    c = small(10, RAGGED, n_q, n_kv, d)
+    print("ragged", n_q, n_kv, d, flush=True)
+    ref, ref_lse = oracle_decode(c)
+    # default plan (mostly unsplit) and a plan forced into many small splits
+    for kw in (dict(), dict(n_cu=64, wg_per_cu=8, min_chunk_blk=1, tile_blk=1, max_split=64),
+               dict(n_cu=8, wg_per_cu=1, min_chunk_blk=4, tile_blk=4, max_split=3)):
+        out, lse = DeviceCase(c, **kw).decode()
+        assert_close(out, ref, f"ragged {kw}")
+        assert_lse_close(lse, ref_lse, f"ragged lse {kw}")
+
+
+def test_lse_output_is_optional():
+    c = small(11, [100, 7], 8, 2, 128)
+    dc = DeviceCase(c)
+    out, lse = dc.decode(want_lse=False)
+    assert np.isnan(lse).all()
+    assert_close(out, oracle_decode(c)[0])
+
+
+def test_needle_at_every_split_and_wave_boundary():
+    """One key dominates the softmax by e^40 and carries a 1000-marker in V: dropping or
+    double counting any token range, or an off-by-one at a boundary, changes the answer."""
+    n_q, n_kv, d = 8, 2, 128
+    L = 3000
+    kw = dict(n_cu=4, wg_per_cu=2, min_chunk_blk=8, tile_blk=4, max_split=64)
+    plan = op.plan_decode([L], n_kv, **kw)
+    assert plan["n_items"] >= 4
+    positions = {0, L - 1, L - 2, (L // 16) * 16 - 1, (L // 16) * 16}
+    for lo, hi in zip(plan["item_blk_begin"], plan["item_blk_end"]):
+        lo, hi = int(lo), int(hi)
+        per_wave = -(-(hi - lo) // 4)
+        for w in range(5):
+            for blk in (lo + w * per_wave - 1, lo + w * per_wave):
+                if lo <= blk < hi:
+                    positions |= {blk * 16, min(blk * 16 + 15, L - 1)}
+    positions = sorted(p for p in positions if 0 <= p < L)
+    print("needle positions", len(positions), flush=True)
+    base = small(12, [L], n_q, n_kv, d, poison=False)
+    G = n_q // n_kv
+    for h in range(n_kv):
+        base["q"][0, h * G:(h + 1) * G] = base["q"][0, h * G]
+    dc = DeviceCase(base, **kw)
+    for pos in positions:
+        c = dict(base)
+        c["pool"] = base["pool"].copy()
+        blk = base["block_ids"][pos // 16]
+        for h in range(n_kv):
+            qv = bits_to_f64(base["q"][0, h * G])
+            c["pool"][blk, h, 0, pos % 16] = hw.f32_to_bf16_bits((40.0 * math.sqrt(d) * qv / (qv @ qv)).astype(np.float32))
+            marker = np.zeros(d, dtype=np.float32)
+            marker[(pos + h) % d] = 1000.0
+            c["pool"][blk, h, 1, pos % 16] = hw.f32_to_bf16_bits(marker)
+        dc.pool.copy_(to_dev_bf16(c["pool"]))
+        out, lse = dc.decode()
+        ref, ref_lse = oracle_decode(c)
+        assert_close(out, ref, f"needle at {pos}")
+        assert_lse_close(lse, ref_lse, f"needle lse at {pos}")
+        for j in range(n_q):
+            assert abs(out[0, j, (pos + j // G) % d] - 1000.0) < 8.0, (pos, j)
+
+
+def test_physical_block_permutation_leaves_output_bits_unchanged():
+    c = small(13, [700, 33, 16, 2500], 8, 2, 128)
+    out1, lse1 = DeviceCase(c).decode()
+    perm = np.random.default_rng(5).permutation(c["n_blocks"])
+    c2 = dict(c)
+    c2["pool"] = np.empty_like(c["pool"])
+    c2["pool"][perm] = c["pool"]
+    c2["block_ids"] = perm[c["block_ids"]].astype(np.int32)
+    out2, lse2 = DeviceCase(c2).decode()
+    assert np.array_equal(out1, out2) and np.array_equal(lse1, lse2)
+
+
+def test_poisoned_tails_and_free_blocks_do_not_leak():
+    lens = [5, 16, 17, 30, 1, 250]
+    c = small(14, lens, 8, 2, 128, poison=True)
+    out, lse = DeviceCase(c).decode()
+    clean = small(14, lens, 8, 2, 128, poison=False)
+    out2, lse2 = DeviceCase(clean).decode()
+    assert np.isfinite(out).all()
+    assert np.array_equal(out, out2) and np.array_equal(lse, lse2)
+
+
+def test_new_row_is_stored_then_attended():
+    lens = [1, 16, 17, 300, 64]
+    c = small(15, lens, 8, 2, 128)
+    rng = np.random.default_rng(3)
+    k_new = hw.f32_to_bf16_bits(rng.standard_normal((5, 2, 128), dtype=np.float32))
+    v_new = hw.f32_to_bf16_bits(rng.standard_normal((5, 2, 128), dtype=np.float32))
+    dc = DeviceCase(c)
+    out, lse = dc.decode(k_new=to_dev_bf16(k_new), v_new=to_dev_bf16(v_new))
+    pool = c["pool"].copy()
+    for b in range(5):
+        oa.write_kv(pool, c["row_off"], c["block_ids"], [lens[b] - 1], b, k_new[b:b + 1], v_new[b:b + 1])
+    assert np.array_equal(dc.pool_bits(), pool)          # exactly those rows changed, bit for bit
+    ref, ref_lse = oracle_decode(c, pool=pool)
+    assert_close(out, ref, "decode with new row")
+    assert_lse_close(lse, ref_lse)
+
+
+def test_invalid_arguments_are_rejected_without_side_effects():
+    import paper_2603_28101_amd as heddle
+    c = small(16, [40, 9], 8, 2, 128)
+    dc = DeviceCase(c)
+    good, _ = dc.decode()
+    before = bf16_to_host_bits(dc.out).copy()
+    for lens in ([0, 9], [40, 17], [131073, 9]):        # zero length; table too short; too long
+        with pytest.raises(heddle.HeddleError) as e:
+            dc.decode(lens=lens)
+        assert e.value.code == heddle.E_INVAL
+    with pytest.raises(heddle.HeddleError):
+        dc.decode(k_new=to_dev_bf16(c["q"][:, :2]))       # k_new without v_new
+    assert np.array_equal(bf16_to_host_bits(dc.out), before)
+    again, _ = dc.decode()
+    assert np.array_equal(good, again)
+
+
+def test_back_to_back_calls_share_scratch_safely():
+    big = small(17, [5000, 4000, 3000, 100], 8, 2, 128)
+    tiny = small(18, [3, 50], 8, 2, 128)
+    d_big, d_tiny = DeviceCase(big), DeviceCase(tiny)
+    ref_big, _ = oracle_decode(big)
+    ref_tiny, _ = oracle_decode(tiny)
+    for _ in range(3):
+        assert_close(d_big.decode()[0], ref_big)
+        assert_close(d_tiny.decode()[0], ref_tiny)
+    # same context, shrinking then growing batch
+    out_small, _ = d_big.decode(lens=[17, 1, 1, 1])
+    assert_close(out_small, oracle_decode(big, lens=[17, 1, 1, 1])[0])
+    assert_close(d_big.decode()[0], ref_big)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_full_size_workloads_sampled(cfg):
+    """The named workloads at full size, in the launch configuration the benchmark times
+    (default plan).  The oracle evaluates sampled (trajectory, head) pairs."""
+    c = hw.make_workload(cfg, 0, threads=16)
+    w = c["workload"]
+    print(f"workload {cfg}: pool {c['pool'].nbytes / 1e9:.2f} GB, tokens {int(c['lens'].sum())}", flush=True)
+    dc = DeviceCase(c)
+    out, lse = dc.decode()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    lens = c["lens"]
+    order = np.argsort(lens)
+    rng = np.random.default_rng(cfg)
+    picks = {int(order[-1]), int(order[-2]), int(order[0]), int(order[len(order) // 2])}
+    picks |= set(int(x) for x in rng.choice(len(lens), 4, replace=False))
+    pairs = [(b, int(j)) for b in sorted(picks) for j in rng.choice(w.n_q_heads, 3, replace=False)]
+    ref, ref_lse = oa.decode_rows(c["pool"], c["row_off"], c["block_ids"], lens, c["q"], w.n_kv_heads, pairs)
+    got = np.array([out[b, j] for b, j in pairs])
+    got_lse = np.array([lse[b, j] for b, j in pairs])
+    assert_close(got, ref, f"workload {cfg}")
+    assert_lse_close(got_lse, ref_lse, f"workload {cfg} lse")
+    # property that holds at any size: sum_t w_t = 1, so |out| never exceeds max |V| (~6 for N(0,1) draws)
+    assert np.abs(out).max() < 8.0

@@ -1,0 +1,192 @@
+"""Host side of the C ABI (no GPU): symbols, block manager, planners, error paths.
+
+The C++ planner and block manager are compared bit for bit with the oracle's."""
+import ctypes
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+import paper_2603_28101_amd as heddle
+from oracle import planner as op
+from oracle.kv_manager import KVManager
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "heddle.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(heddle_[a-z_]+)\s*\(", text)))
+    assert {"heddle_kv_alloc", "heddle_kv_free", "heddle_attn_decode", "heddle_attn_append",
+            "heddle_plan_decode", "heddle_ctx_create"} <= set(names)
+    lib = ctypes.CDLL(heddle.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.heddle_version() >= 1
+
+
+def host_ctx(n_q=32, n_kv=8, d=128, n_blocks=64, **kw):
+    return heddle.Context(n_q, n_kv, d, n_blocks, **kw)
+
+
+def test_strerror_and_create_errors():
+    assert heddle.lib.heddle_strerror(0) == b"ok"
+    assert b"invalid" in heddle.lib.heddle_strerror(heddle.E_INVAL)
+    for bad in (dict(n_q=6, n_kv=4), dict(n_blocks=0), dict(d=7)):
+        with pytest.raises(heddle.HeddleError) as e:
+            host_ctx(**bad)
+        assert e.value.code == heddle.E_INVAL
+    with pytest.raises(heddle.HeddleError):     # device context without a pool
+        heddle.Context(8, 2, 64, 4, kv_pool=None, device=0)
+
+
+def test_attention_on_host_only_context_is_refused():
+    c = host_ctx()
+    with pytest.raises(heddle.HeddleError) as e:
+        c.attn_decode([5], [0, 1], 0x1000, 0x1000, 0x1000, 0x1000, stream=0)
+    assert e.value.code == heddle.E_UNSUPPORTED
+
+
+# ------------------------------------------------------------- block manager
+
+def test_manager_golden_traces_on_library():
+    traces = json.load(open(os.path.join(GOLDEN, "kv_manager_traces.json")))["traces"]
+    for tr in traces:
+        c = host_ctx(n_blocks=tr["n_blocks"])
+        for o in tr["ops"]:
+            if o[0] == "alloc":
+                if o[2] == 0:
+                    assert c.kv_alloc(o[1]).tolist() == o[3], o
+                else:
+                    with pytest.raises(heddle.HeddleError) as e:
+                        c.kv_alloc(o[1])
+                    assert e.value.code == o[2], o
+            elif o[0] == "free":
+                if o[2] == 0:
+                    c.kv_free(o[1])
+                else:
+                    with pytest.raises(heddle.HeddleError) as e:
+                        c.kv_free(o[1])
+                    assert e.value.code == o[2], o
+            else:
+                assert c.kv_num_free() == o[1], o
+
+
+def test_manager_random_scripts_match_oracle():
+    rng = np.random.default_rng(1)
+    for trial in range(20):
+        n = int(rng.integers(1, 200))
+        c, m = host_ctx(n_blocks=n), KVManager(n)
+        held = []
+        for step in range(400):
+            r = rng.random()
+            if r < 0.45:
+                k = int(rng.integers(0, n // 2 + 2))
+                code, ids = m.alloc(k)
+                try:
+                    got = c.kv_alloc(k).tolist()
+                    assert code == 0 and got == ids
+                    held += ids
+                except heddle.HeddleError as e:
+                    assert e.code == code != 0
+            elif r < 0.9 and held:
+                k = int(rng.integers(1, len(held) + 1))
+                idx = rng.permutation(len(held))[:k].tolist()
+                ids = [held[i] for i in idx]
+                if rng.random() < 0.15:          # corrupt: duplicate / foreign / out of range
+                    ids = ids + [ids[0]] if rng.random() < 0.5 else ids + [int(rng.integers(-3, n + 3))]
+                code = m.free(ids)
+                try:
+                    c.kv_free(ids)
+                    assert code == 0
+                    held = [h for h in held if h not in set(ids)]
+                except heddle.HeddleError as e:
+                    assert e.code == code != 0
+            assert c.kv_num_free() == m.num_free()
+
+
+# ------------------------------------------------------------------ planners
+
+def same_plan(a, b):
+    assert a["chunk"] == b["chunk"] and a["n_items"] == b["n_items"]
+    for k in ("item_b", "item_s", "item_blk_begin", "item_blk_end", "nsplit", "part_off"):
+        assert np.array_equal(a[k], b[k]), k
+        assert a[k].dtype == np.int32
+
+
+def test_plan_golden_examples_on_library():
+    for ex in json.load(open(os.path.join(GOLDEN, "plan_worked_examples.json")))["examples"]:
+        p = dict(ex["params"])
+        c = heddle.Context(p["n_kv_heads"], p["n_kv_heads"], 128, 4, n_cu=p["n_cu"], wg_per_cu=p["wg_per_cu"],
+                           min_chunk_blk=p["min_chunk_blk"], tile_blk=p["tile_blk"], max_split=p["max_split"])
+        plan = c.plan_decode(ex["lens"])
+        assert plan["chunk"] == ex["chunk"]
+        for key in ("nsplit", "part_off", "item_b", "item_s", "item_blk_begin", "item_blk_end"):
+            assert plan[key].tolist() == ex[key], key
+
+
+def test_plan_named_workloads_match_oracle():
+    for cfg in (1, 2, 3, 4):
+        w = hw.WORKLOADS[cfg]
+        for seed in (0, 1, 2):
+            lens, _ = hw.workload_lengths(cfg, seed)
+            c = host_ctx(w.n_q_heads, w.n_kv_heads, w.head_dim, n_cu=256)
+            same_plan(c.plan_decode(lens), op.plan_decode(lens, w.n_kv_heads, **op.DEFAULTS))
+
+
+def test_plan_exhaustive_small_matches_oracle():
+    kw = dict(n_cu=2, wg_per_cu=3, min_chunk_blk=1, tile_blk=2, max_split=4)
+    c = heddle.Context(1, 1, 64, 4, **kw)
+    for a in range(1, 201, 9):
+        for b in range(1, 201, 5):
+            for d in (1, 16, 17, 200):
+                lens = [a, b, d]
+                same_plan(c.plan_decode(lens), op.plan_decode(lens, 1, **kw))
+
+
+def test_plan_random_long_tail_matches_oracle():
+    rng = np.random.default_rng(7)
+    for trial in range(400):
+        B = int(rng.integers(1, 300))
+        lens = np.clip(np.rint(np.exp(rng.normal(np.log(3000), 1.4, B))), 1, 131072).astype(np.int64)
+        kw = dict(n_cu=int(rng.integers(1, 400)), wg_per_cu=int(rng.integers(1, 9)),
+                  min_chunk_blk=int(rng.integers(1, 64)), tile_blk=int(rng.choice([1, 2, 4, 8])),
+                  max_split=int(rng.integers(1, 80)))
+        n_kv = int(rng.choice([1, 2, 4, 8]))
+        c = heddle.Context(n_kv, n_kv, 128, 4, **kw)
+        same_plan(c.plan_decode(lens), op.plan_decode(lens, n_kv, **kw))
+
+
+def test_plan_errors():
+    c = host_ctx()
+    for lens in ([0], [5, -1], [131073]):
+        with pytest.raises(heddle.HeddleError) as e:
+            c.plan_decode(lens)
+        assert e.value.code == heddle.E_INVAL
+    c.plan_decode([131072])
+
+
+def test_append_order_matches_oracle():
+    rng = np.random.default_rng(9)
+    c = host_ctx()
+    for trial in range(100):
+        B = int(rng.integers(1, 40))
+        L = rng.integers(0, 60000, B)
+        Cn = rng.integers(1, 1025, B)
+        cu = np.concatenate([[0], np.cumsum(Cn)])
+        R = int(rng.choice([16, 32, 64]))
+        a, b = c.plan_append(L, cu, R), op.plan_append(L, Cn, R)
+        assert a["n_tiles"] == b["n_tiles"] and a["tile_rows"] == R
+        for k in ("tile_b", "tile_row0", "tile_rows_n", "tile_extent"):
+            assert np.array_equal(a[k], b[k]), k
+    # default tile height: 128 MFMA rows shared by the G heads of a group
+    assert c.plan_append([10], [0, 100])["tile_rows"] == 32
+    with pytest.raises(heddle.HeddleError):
+        c.plan_append([10], [0, 0], 32)          # empty chunk
+    with pytest.raises(heddle.HeddleError):
+        c.plan_append([-1], [0, 4], 32)
