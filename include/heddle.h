@@ -194,6 +194,8 @@ int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* 
 int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream);
 
 const char* heddle_strerror(int code);
+/* Text of the HIP call that made the calling thread's last HEDDLE_E_HIP (empty if none). */
+const char* heddle_last_error_detail(void);
 int heddle_version(void);
 
 #ifdef __cplusplus

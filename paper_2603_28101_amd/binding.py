@@ -16,6 +16,10 @@ def lib_path() -> str:
 
 
 def _load():
+    # PyTorch ships its own HIP runtime; two runtimes in one process cannot both open the
+    # GPU.  Import torch first so that libheddle's libamdhip64.so.7 dependency resolves to
+    # the copy torch has already loaded.
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError(
@@ -88,6 +92,7 @@ lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINT
 lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
+lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_append", "heddle_timing_enable", "heddle_timing_read", "heddle_stream_read",
@@ -98,7 +103,8 @@ for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle
 class HeddleError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {lib.heddle_strerror(code).decode()} ({code})")
+        detail = lib.heddle_last_error_detail().decode() if code == E_HIP else ""
+        super().__init__(f"{where}: {lib.heddle_strerror(code).decode()} ({code}) {detail}")
 
 
 def _check(code: int, where: str):

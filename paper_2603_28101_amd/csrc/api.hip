@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -60,9 +61,17 @@ struct heddle_ctx {
 
 namespace {
 
-#define HEDDLE_HIP(expr)                         \
-  do {                                           \
-    if ((expr) != hipSuccess) return HEDDLE_E_HIP; \
+thread_local char g_detail[256] = "";
+
+int hip_failed(hipError_t e, const char* what, int line) {
+  std::snprintf(g_detail, sizeof(g_detail), "%s -> %s (line %d)", what, hipGetErrorString(e), line);
+  return HEDDLE_E_HIP;
+}
+
+#define HEDDLE_HIP(expr)                                                \
+  do {                                                                  \
+    const hipError_t heddle_hip_e = (expr);                             \
+    if (heddle_hip_e != hipSuccess) return hip_failed(heddle_hip_e, #expr, __LINE__); \
   } while (0)
 
 class DeviceGuard {
@@ -323,7 +332,7 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   if (rc != HEDDLE_OK) return rc;
 
   // plan image: lens[B] | first_pos[B] | cu_rows[B+1] | part_off[B+1] | nsplit[B] | 4 x items
-  const size_t words = 4 * static_cast<size_t>(B) + 2 + 4 * n_items;
+  const size_t words = 5 * static_cast<size_t>(B) + 2 + 4 * n_items;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
@@ -469,6 +478,8 @@ const char* heddle_strerror(int code) {
     default: return "unknown error";
   }
 }
+
+const char* heddle_last_error_detail(void) { return g_detail; }
 
 int heddle_version(void) { return 1; }
 
