@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the trajectory-generation attention hot path on one MI355X.
+
+A step is one pass of the whole decode hot path over one batch: host split-K plan, plan
+upload, split-K decode kernel, log-sum-exp combine kernel (one heddle_attn_decode call),
+on the Qwen3-8B-shaped long-tail workload (64 trajectories, 32 query / 8 kv heads,
+head_dim 128, lognormal context lengths).  Inputs are synthetic and resident in HBM
+before the timed region.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4|5] [--seed S]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (no sharding or collectives are built); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import heddle_workloads as hw
+    import paper_2603_28101_amd as heddle
+
+    torch.cuda.set_device(0)
+    w = hw.WORKLOADS[args.workload]
+    case = hw.make_workload(args.workload, args.seed, threads=min(16, os.cpu_count() or 1))
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def dev_i32(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+    pool = dev_bf16(case["pool"])
+    row_off, block_ids, q = dev_i32(case["row_off"]), dev_i32(case["block_ids"]), dev_bf16(case["q"])
+    out = torch.empty(case["q"].shape, dtype=torch.bfloat16, device="cuda")
+    ctx = heddle.Context(w.n_q_heads, w.n_kv_heads, w.head_dim, case["n_blocks"], kv_pool=pool, device=0)
+    stream = torch.cuda.current_stream()
+
+    if w.kind == "decode":
+        lens = case["lens"]
+        unit_bytes = hw.kv_bytes(lens, w.n_kv_heads, w.head_dim)   # algorithmic bytes of one step
+
+        def step():
+            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+
+        dominant, bound = 0, "hbm"
+    else:
+        k_new, v_new = dev_bf16(case["k_new"]), dev_bf16(case["v_new"])
+        L, cu = case["lens"], case["cu_chunk"]
+        C = case["chunk_lens"].astype(np.int64)
+        # 4*d*Hq flops per (query row, visible key) pair; causal part counted once
+        unit_flops = int(4 * w.head_dim * w.n_q_heads * (C * (L.astype(np.int64) + (C + 1) / 2)).sum())
+        unit_bytes = hw.kv_bytes(L.astype(np.int64) + C, w.n_kv_heads, w.head_dim)
+
+        def step():
+            ctx.attn_append(L, cu, case["row_off"], row_off, block_ids, q, k_new, v_new, out, None, stream=stream)
+
+        dominant, bound = 2, "mfma"
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)            # HIP events around each kernel, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_us, n_launch = ctx.timing_read(dominant)
+    aux_us = ctx.timing_read(1)[0] if w.kind == "decode" else ctx.timing_read(3)[0]
+    ctx.timing_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if w.kind == "decode":
+        value = unit_bytes / (ms_per_step * 1e-3) / 1e9
+        metric, unit = "decode-attention KV GB/s", "GB/s"
+        achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
+        roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "kernel": "decode_splitk_kernel", "kernel_avg_us": round(kernel_us, 2),
+                    "launches_timed": n_launch, "combine_avg_us": round(aux_us, 2)}
+    else:
+        value = unit_flops / (ms_per_step * 1e-3) / 1e12
+        metric, unit = "append-attention TFLOP/s", "TFLOP/s"
+        achieved = unit_flops / (kernel_us * 1e-6) / 1e12
+        roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "kernel": "append_attn_kernel", "kernel_avg_us": round(kernel_us, 2),
+                    "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2)}
+
+    # measured streaming-read ceiling over the same pool (context for the fraction above)
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    nbytes = pool.numel() * 2
+    for _ in range(3):
+        heddle.stream_read(pool, nbytes, sink, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        heddle.stream_read(pool, nbytes, sink, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbps = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    result = {
+        "metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name} (config {w.cfg_id}, seed {args.seed})", "trajectories": w.B,
+                   "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "kv_bytes_per_step": unit_bytes, "tokens": int(np.asarray(case["lens"], dtype=np.int64).sum())},
+        "us_per_step": round(ms_per_step * 1e3, 1),
+        "frac_of_hbm_peak_whole_step": round(unit_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "stream_read_ceiling_GBps": round(stream_gbps, 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(case, w, np)
+    print(json.dumps(result))
+
+
+def cpu_baseline(case, w, np):
+    """The float64 oracle as it stands, timed on this host on a bounded sample."""
+    from oracle import attention as oa
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        blas_threads = 1
+    budget_s = 20.0
+    t0 = time.perf_counter()
+    if w.kind == "decode":
+        lens = case["lens"]
+        done_bytes, n_done = 0, 0
+        for b in range(len(lens)):
+            pairs = [(b, j) for j in range(w.n_q_heads)]
+            oa.decode_rows(case["pool"], case["row_off"], case["block_ids"], lens, case["q"], w.n_kv_heads, pairs)
+            done_bytes += int(lens[b]) * 2 * w.n_kv_heads * w.head_dim * 2
+            n_done += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        dt = time.perf_counter() - t0
+        return {"value": round(done_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": blas_threads, "kind": "oracle",
+                "sample": f"first {n_done} of {len(lens)} trajectories, all heads ({done_bytes} KV bytes in {dt:.1f} s)",
+                "host_cpus": os.cpu_count(), "affinity": len(os.sched_getaffinity(0))}
+    # append: all trajectories would take minutes; evaluate a fixed row subset of the first ones
+    pool = case["pool"].copy()
+    L, cu = case["lens"], case["cu_chunk"]
+    rows = []
+    for b in range(len(L)):
+        C = int(cu[b + 1] - cu[b])
+        rows += [int(cu[b]) + r for r in sorted({0, 1, C - 2, C - 1} | set(range(0, C, 97))) if 0 <= r < C]
+    flops = 0
+    done_rows = 0
+    for r in rows:
+        b = int(np.searchsorted(cu, r, side="right") - 1)
+        oa.append(pool, case["row_off"], case["block_ids"], L, cu, case["q"], case["k_new"], case["v_new"],
+                  w.n_kv_heads, rows=[r])
+        flops += 4 * w.head_dim * w.n_q_heads * (int(L[b]) + r - int(cu[b]) + 1)
+        done_rows += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": blas_threads, "kind": "oracle",
+            "sample": f"{done_rows} sampled chunk rows, all heads ({dt:.1f} s, includes the oracle's KV write each call)",
+            "host_cpus": os.cpu_count(), "affinity": len(os.sched_getaffinity(0))}
+
+
+if __name__ == "__main__":
+    main()
