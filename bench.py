@@ -12,6 +12,7 @@ before the timed region.  Prints one JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -63,7 +64,9 @@ def main():
     row_off, block_ids, q = dev_i32(case["row_off"]), dev_i32(case["block_ids"]), dev_bf16(case["q"])
     out = torch.empty(case["q"].shape, dtype=torch.bfloat16, device="cuda")
     ctx = heddle.Context(w.n_q_heads, w.n_kv_heads, w.head_dim, case["n_blocks"], kv_pool=pool, device=0)
-    stream = torch.cuda.current_stream()
+    # a stream of its own: work queued on the null stream pays for its implicit
+    # synchronisation with every other stream of the process
+    stream = torch.cuda.Stream()
 
     if w.kind == "decode":
         lens = case["lens"]
@@ -86,16 +89,22 @@ def main():
 
         dominant, bound = 2, "mfma"
 
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     ctx.timing_enable(True)            # HIP events around each kernel, on the launch stream
+    # a full Python garbage collection (tens of ms with torch loaded) must not land in the
+    # timed region: collect now, keep the collector off while timing
+    gc.collect()
+    gc.disable()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     aux_us = ctx.timing_read(1)[0] if w.kind == "decode" else ctx.timing_read(3)[0]
     ctx.timing_enable(False)
@@ -124,10 +133,10 @@ def main():
     for _ in range(3):
         heddle.stream_read(pool, nbytes, sink, stream)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
+    e0.record(stream)
     for _ in range(10):
         heddle.stream_read(pool, nbytes, sink, stream)
-    e1.record()
+    e1.record(stream)
     torch.cuda.synchronize()
     stream_gbps = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 

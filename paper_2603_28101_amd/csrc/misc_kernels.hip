@@ -35,17 +35,26 @@ __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
   }
 }
 
-constexpr int kStreamGroups = 4096;
+constexpr int kStreamGroups = 2048;
+constexpr int kStreamUnroll = 8;
 
+// Contiguous 32 KB tiles (256 threads x 8 x 16 B) taken round robin by the workgroups, all
+// eight loads of a thread in flight at once, non-temporal like the decode kernel's KV loads.
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, uint64_t n_vec, uint32_t* sink) {
   uint32_t x = 0;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-  uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  for (; i + 3 * stride < n_vec; i += 4 * stride) {
-    const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-    x ^= v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+  const uint64_t tile_vec = 256ull * kStreamUnroll;
+  const uint64_t n_tiles = n_vec / tile_vec;
+  for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const u32x4* p = src + t * tile_vec + threadIdx.x;
+    u32x4 v[kStreamUnroll];
+#pragma unroll
+    for (int i = 0; i < kStreamUnroll; ++i) v[i] = __builtin_nontemporal_load(p + i * 256);
+#pragma unroll
+    for (int i = 0; i < kStreamUnroll; ++i) x ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
   }
-  for (; i < n_vec; i += stride) {
+  // remainder shorter than a tile
+  for (uint64_t i = n_tiles * tile_vec + static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_vec;
+       i += static_cast<uint64_t>(gridDim.x) * blockDim.x) {
     const u32x4 v = src[i];
     x ^= v.x ^ v.y ^ v.z ^ v.w;
   }
