@@ -55,6 +55,19 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return (rounded >> np.uint32(16)).astype(np.uint16)
 
 
+def k_view(pool: np.ndarray) -> np.ndarray:
+    """K tiles of a pool as [n_blocks][n_kv][16 tokens][d] (a view)."""
+    nb, nkv, _, n = pool.shape
+    return pool[:, :, 0, :].reshape(nb, nkv, BLOCK_TOKENS, n // BLOCK_TOKENS)
+
+
+def v_view(pool: np.ndarray) -> np.ndarray:
+    """V tiles of a pool as [n_blocks][n_kv][d][16 tokens] (a view): V is stored transposed,
+    the 16 tokens of one head-dim element are contiguous."""
+    nb, nkv, _, n = pool.shape
+    return pool[:, :, 1, :].reshape(nb, nkv, n // BLOCK_TOKENS, BLOCK_TOKENS)
+
+
 def _lognormal_lengths(rng, n, median, sigma, lo, hi):
     x = np.exp(rng.normal(math.log(median), sigma, n))
     return np.clip(np.rint(x), lo, hi).astype(np.int64)
@@ -131,7 +144,8 @@ def build_case(
                 the chunk are left poisoned in the pool.
 
     Returns a dict of numpy arrays:
-      pool       uint16 [n_blocks][n_kv][2][16][d]   (bf16 bits; index 2: K, V)
+      pool       uint16 [n_blocks][n_kv][2][16*d]    (bf16 bits; index 2 = 0: K tile, token-major
+                 [16][d]; index 2 = 1: V tile, transposed [d][16]; see k_view / v_view)
       row_off    int32  [B+1]   CSR offsets into block_ids
       block_ids  int32  [row_off[B]]
       lens       int32  [B]
@@ -170,7 +184,7 @@ def build_case(
         out["chunk_lens"] = chunk_lens.astype(np.int32)
         out["cu_chunk"] = cu.astype(np.int32)
 
-    pool = np.empty((n_blocks, n_kv_heads, 2, BLOCK_TOKENS, head_dim), dtype=np.uint16)
+    pool = np.empty((n_blocks, n_kv_heads, 2, BLOCK_TOKENS * head_dim), dtype=np.uint16)
     ent = list(entropy) if isinstance(entropy, (list, tuple)) else [int(entropy)]
     _fill_pool(pool, ent + [0x6B76], threads)
 
@@ -187,7 +201,8 @@ def build_case(
             blk, slot = divmod(first, BLOCK_TOKENS)
             if blk < len(row):
                 if slot:
-                    pool[row[blk], :, :, slot:, :] = POISON_NAN
+                    k_view(pool)[row[blk], :, slot:, :] = POISON_NAN
+                    v_view(pool)[row[blk], :, :, slot:] = POISON_NAN
                     blk += 1
                 if blk < len(row):
                     pool[row[blk:]] = POISON_NAN

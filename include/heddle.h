@@ -22,7 +22,9 @@
  *
  * Memory layout (all device pointers are caller-owned; the library allocates
  * only its own context, a small pinned staging ring and grow-only scratch):
- *   kv_pool    bf16 [n_blocks][n_kv_heads][2][16][head_dim]   index 2: 0 = K, 1 = V
+ *   kv_pool    bf16 [n_blocks][n_kv_heads][2][16 * head_dim]; per (block, kv head) a K tile,
+ *              token-major [16][head_dim], followed by a V tile stored transposed,
+ *              [head_dim][16] (the 16 tokens of one head-dim element are contiguous)
  *   block table in CSR form: token position p of trajectory b is stored in
  *              block  block_ids[row_off[b] + p / 16], slot p % 16
  *   q / out    bf16 [rows][n_q_heads][head_dim]

@@ -4,7 +4,8 @@ TEST INFRASTRUCTURE ONLY (see package docstring).
 Conventions (the paper fixes none of these; it delegates generation to an
 inference engine, Sec. 7 "Implementation", and cites paged attention, Sec. 9):
 
-  pool       uint16 [n_blocks][n_kv][2][16][d]  bf16 bit patterns, 2 = (K, V)
+  pool       uint16 [n_blocks][n_kv][2][16*d]  bf16 bit patterns; [..][0] is the K tile,
+             token-major [16][d]; [..][1] is the V tile stored transposed, [d][16]
   table      CSR: block_ids[row_off[b] + p // 16] is the physical block that
              holds token position p of trajectory b, slot p % 16
   heads      query head j reads kv head j // (n_q / n_kv)
@@ -35,9 +36,13 @@ def gather(pool_bits, row_off, block_ids, b: int, length: int):
     row = np.asarray(block_ids[row_off[b]:row_off[b + 1]])
     if nblk > row.shape[0]:
         raise ValueError("block table row shorter than the context")
-    blocks = pool_bits[row[:nblk]]                       # [nblk][n_kv][2][16][d]
-    n_kv, d = blocks.shape[1], blocks.shape[4]
-    kv = blocks.transpose(2, 1, 0, 3, 4).reshape(2, n_kv, nblk * BLOCK_TOKENS, d)
+    blocks = pool_bits[row[:nblk]]                       # [nblk][n_kv][2][16*d]
+    n_kv = blocks.shape[1]
+    d = blocks.shape[3] // BLOCK_TOKENS
+    k_tiles = blocks[:, :, 0, :].reshape(nblk, n_kv, BLOCK_TOKENS, d)
+    v_tiles = blocks[:, :, 1, :].reshape(nblk, n_kv, d, BLOCK_TOKENS).transpose(0, 1, 3, 2)
+    kv = np.stack([k_tiles, v_tiles])                    # [2][nblk][n_kv][16][d]
+    kv = kv.transpose(0, 2, 1, 3, 4).reshape(2, n_kv, nblk * BLOCK_TOKENS, d)
     kv = bf16_bits_to_f64(kv[:, :, :length, :])
     return kv[0], kv[1]
 
@@ -53,39 +58,54 @@ def attend(q, K, V, scale):
     return w @ V, m + math.log(denom), w
 
 
-def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=None):
+def weight_spread(w, V, out):
+    """sqrt(sum_t w_t^2 (V[t] - out)^2) per output element: the standard deviation of the
+    output under independent unit-variance relative perturbations of the weights (first
+    order, numerator and denominator perturbed alike).  The tests use it to bound what
+    rounding the weights to bf16 may do to the result."""
+    return np.sqrt((w * w) @ ((V - out) ** 2))
+
+
+def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=None, with_spread=False):
     """One new token per trajectory.  q_bits uint16 [B][n_q][d].
-    Returns out float64 [B][n_q][d], lse float64 [B][n_q]."""
+    Returns out float64 [B][n_q][d], lse float64 [B][n_q] (and weight_spread [B][n_q][d])."""
     B, n_q, d = q_bits.shape
     G = n_q // n_kv_heads
     s = 1.0 / math.sqrt(d) if scale is None else float(scale)
     q = bf16_bits_to_f64(q_bits)
     out = np.zeros((B, n_q, d))
     lse = np.zeros((B, n_q))
+    spread = np.zeros((B, n_q, d))
     for b in range(B):
         if lens[b] < 1:
             raise ValueError("decode needs len >= 1")
         K, V = gather(pool_bits, row_off, block_ids, b, int(lens[b]))
         for j in range(n_q):
-            out[b, j], lse[b, j], _ = attend(q[b, j], K[j // G], V[j // G], s)
-    return out, lse
+            out[b, j], lse[b, j], w = attend(q[b, j], K[j // G], V[j // G], s)
+            if with_spread:
+                spread[b, j] = weight_spread(w, V[j // G], out[b, j])
+    return (out, lse, spread) if with_spread else (out, lse)
 
 
-def decode_rows(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads, pairs, scale=None):
+def decode_rows(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads, pairs, scale=None, with_spread=False):
     """decode() restricted to a list of (b, j) pairs; for sampled checks on
     batches too large to evaluate in full."""
     _, n_q, d = q_bits.shape
     G = n_q // n_kv_heads
     s = 1.0 / math.sqrt(d) if scale is None else float(scale)
-    outs, lses = [], []
+    outs, lses, spreads = [], [], []
     cache = {}
     for b, j in pairs:
         if b not in cache:
             cache = {b: gather(pool_bits, row_off, block_ids, b, int(lens[b]))}
         K, V = cache[b]
-        o, l, _ = attend(bf16_bits_to_f64(q_bits[b, j]), K[j // G], V[j // G], s)
+        o, l, w = attend(bf16_bits_to_f64(q_bits[b, j]), K[j // G], V[j // G], s)
         outs.append(o)
         lses.append(l)
+        if with_spread:
+            spreads.append(weight_spread(w, V[j // G], o))
+    if with_spread:
+        return np.array(outs), np.array(lses), np.array(spreads)
     return np.array(outs), np.array(lses)
 
 
@@ -134,12 +154,13 @@ def write_kv(pool_bits, row_off, block_ids, positions, b: int, k_bits, v_bits):
         blk, slot = divmod(int(p), BLOCK_TOKENS)
         if blk >= row.shape[0]:
             raise ValueError("block table row too short for the appended token")
-        pool_bits[row[blk], :, 0, slot, :] = k_bits[i]
-        pool_bits[row[blk], :, 1, slot, :] = v_bits[i]
+        n_kv, d = k_bits.shape[1], k_bits.shape[2]
+        pool_bits[row[blk], :, 0, :].reshape(n_kv, BLOCK_TOKENS, d)[:, slot, :] = k_bits[i]
+        pool_bits[row[blk], :, 1, :].reshape(n_kv, d, BLOCK_TOKENS)[:, :, slot] = v_bits[i]
 
 
 def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_bits,
-           n_kv_heads: int, scale=None, rows=None):
+           n_kv_heads: int, scale=None, rows=None, with_spread=False):
     """Append a chunk per trajectory: first store the chunk's K/V rows at
     positions L_b .. L_b + C_b - 1 (pool_bits is modified in place), then each
     chunk row attends causally: row i of trajectory b sees L_b + i + 1 keys.
@@ -161,6 +182,7 @@ def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_
     want = None if rows is None else set(int(r) for r in rows)
     out = np.zeros((n_rows, n_q, d))
     lse = np.zeros((n_rows, n_q))
+    spread = np.zeros((n_rows, n_q, d)) if with_spread else None
     for b in range(B):
         lo, hi = int(cu_chunk[b]), int(cu_chunk[b + 1])
         L = int(ctx_lens[b])
@@ -172,13 +194,15 @@ def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_
             n_keys = L + (r - lo) + 1
             qr = bf16_bits_to_f64(q_bits[r])
             for j in range(n_q):
-                out[r, j], lse[r, j], _ = attend(qr[j], K[j // G][:n_keys], V[j // G][:n_keys], s)
-    return out, lse
+                out[r, j], lse[r, j], w = attend(qr[j], K[j // G][:n_keys], V[j // G][:n_keys], s)
+                if with_spread:
+                    spread[r, j] = weight_spread(w, V[j // G][:n_keys], out[r, j])
+    return (out, lse, spread) if with_spread else (out, lse)
 
 
 def pack(pool_bits, row_off, block_ids, b: int, length: int):
     """Contiguous copy of trajectory b's first ceil(length/16) blocks, in table
-    order: uint16 [nblk][n_kv][2][16][d].  (Staging form of a trajectory's
+    order: uint16 [nblk][n_kv][2][16*d].  (Staging form of a trajectory's
     cache for eviction or migration, Sec. 4.2 / Sec. 5.3.)"""
     nblk = (length + BLOCK_TOKENS - 1) // BLOCK_TOKENS
     row = np.asarray(block_ids[row_off[b]:row_off[b + 1]])[:nblk]

@@ -327,7 +327,7 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems,
                        n_parts * Hq * D, sizeof(float));
   if (rc != HEDDLE_OK) return rc;
-  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 2,
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 4,
                    sizeof(float));
   if (rc != HEDDLE_OK) return rc;
 

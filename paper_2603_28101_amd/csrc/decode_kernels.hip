@@ -10,15 +10,22 @@
 // The loads are non-temporal: the data is never reused, and on this chip a read stream
 // that bypasses cache retention runs about 12 % faster than one that does not.
 //
-// Lane layout (wave64): a K or V row of d bf16 is covered by d/8 lanes holding 8 elements
-// (16 bytes) each, so one wave load instruction brings 64*16 B = 1 KB = 1024/(2d) token
-// rows.  Each lane forms G partial dot products with packed-bf16 dot instructions, the
-// d/8 lanes of a row are summed with DPP adds, and the same lane layout is reused for
-// V, so P*V needs no data movement: acc[g][8] += p[g] * v[8].
-//
-// Softmax runs in base 2 with a lazily updated reference maximum per head: the reference
-// only moves (and the accumulators are only rescaled) when some logit exceeds it by more
-// than 2^8, which is rare after the first few blocks; p is then at most 256.
+// Per 16-token block and wave (wave64):
+//   Q.K   The K tile is token-major [16][d]; a row of d bf16 is covered by d/8 lanes holding
+//         8 elements (16 bytes) each.  Every lane forms G partial dot products per load with
+//         packed-bf16 dot instructions.  The partials of a row are then summed with a
+//         reduce-scatter over its lanes (DPP adds): each step halves the number of values a
+//         lane carries, so a lane ends with the complete logit of one (token, head) pair (two
+//         for G = 8) instead of every lane ending with all of them.
+//   softmax  runs once per (token, head), in base 2, against a lazily updated reference
+//         maximum per head: the reference moves (and accumulators are rescaled) only when a
+//         logit exceeds it by more than 2^8, which is rare after the first blocks.
+//   P.V   The V tile is stored transposed, [d][16]: a lane's 16 bytes are 8 consecutive tokens
+//         of one head-dim element, so P.V is again packed-bf16 dot products, acc[g][e] +=
+//         p[g][t..t+1] . v[e][t..t+1], with p rounded to bf16 and passed between lanes through
+//         a 32-byte-per-head LDS row private to the wave.  The softmax denominator used for
+//         the output is the sum of the same rounded p (so the weights stay normalised); the
+//         log-sum-exp output uses the unrounded sum.
 #include "kernels.h"
 
 namespace heddle {
@@ -30,7 +37,14 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kBlockTokens = 16;
 constexpr int kWavesPerGroup = 4;
+constexpr int kSameHeadStride = 4;      // lanes l and l + 4k carry the same query head(s)
 constexpr float kLazyMaxSlack = 8.0f;   // log2 units
+
+// Lanes of one wave exchange values through LDS without a hardware barrier: the LDS executes
+// a wave's instructions in order, so a read issued after a write sees it.  The compiler must
+// still be told that memory may have changed under it (other lanes wrote), or it forwards a
+// lane's own store into its later load and hoists loads above stores of other lanes.
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {
@@ -38,26 +52,138 @@ __device__ __forceinline__ float dpp_add(float x) {
   return x + __builtin_bit_cast(float, moved);
 }
 
-// Sum over the LPR consecutive lanes that hold one token row; every lane gets the sum.
-// N independent values go through each step together so that the two wait states a DPP
-// read needs after a VALU write are filled by the neighbouring chains.
-template <int LPR, int N>
-__device__ __forceinline__ void row_sum(float (&x)[N]) {
-  if constexpr (LPR == 16) {
-#pragma unroll
-    for (int n = 0; n < N; ++n) x[n] = dpp_add<0x128>(x[n]);   // row_ror:8
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <- lane 7 - i within each 8 lanes
+constexpr int kDppMirror = 0x140;       // lane i <- lane 15 - i within each 16 lanes
+
+// One halving step of the reduce-scatter across lane pairs (i, 15 - i) [FULL] or (i, 7 - i)
+// within 8 lanes [!FULL].  The lane of a pair that sits in the lower half keeps lo, the other
+// keeps hi; both receive own + partner for the value they keep.  Two DPP adds with
+// complementary bank masks write the two halves of the same destination register.  The
+// leading s_nop covers the wait states a DPP read needs after the dot instructions that
+// produced the inputs; inline assembly is not covered by the compiler's hazard handling.
+template <bool FULL>
+__device__ __forceinline__ void pair_reduce4(float& o0, float& o1, float& o2, float& o3, float l0, float l1,
+                                             float l2, float l3, float h0, float h1, float h2, float h3) {
+  if constexpr (FULL) {
+    asm("s_nop 4\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+        "s_nop 1"
+        : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+        : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
+  } else {
+    asm("s_nop 4\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "s_nop 1"
+        : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+        : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
   }
-#pragma unroll
-  for (int n = 0; n < N; ++n) x[n] = dpp_add<0x141>(x[n]);     // row_half_mirror
-#pragma unroll
-  for (int n = 0; n < N; ++n) x[n] = dpp_add<0xB1>(x[n]);      // quad_perm [1,0,3,2]
-#pragma unroll
-  for (int n = 0; n < N; ++n) x[n] = dpp_add<0x4E>(x[n]);      // quad_perm [2,3,0,1]
 }
 
-__device__ __forceinline__ float wave_max(float x) {
+template <bool FULL>
+__device__ __forceinline__ void pair_reduce1(float& o, float lo, float hi) {
+  if constexpr (FULL) {
+    asm("s_nop 4\n\t"
+        "v_add_f32_dpp %0, %1, %1 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %2, %2 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+        "s_nop 1"
+        : "=&v"(o)
+        : "v"(lo), "v"(hi));
+  } else {
+    asm("s_nop 4\n\t"
+        "v_add_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %0, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+        "s_nop 1"
+        : "=&v"(o)
+        : "v"(lo), "v"(hi));
+  }
+}
+
+constexpr int half_or_one(int n) { return n > 1 ? n / 2 : 1; }
+
+// in[CNT] -> out[max(CNT/2,1)] across mirror pairs; with a single value left it is summed
+// into both lanes instead (all-reduce step).
+template <bool FULL, int CNT>
+__device__ __forceinline__ void level_mirror(const float (&in)[CNT], float (&out)[half_or_one(CNT)]) {
+  if constexpr (CNT == 1) {
+    out[0] = dpp_add<FULL ? kDppMirror : kDppHalfMirror>(in[0]);
+  } else {
+    constexpr int H = CNT / 2;
+    if constexpr (H % 4 == 0) {
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+      for (int k = 0; k < H; k += 4)
+        pair_reduce4<FULL>(out[k], out[k + 1], out[k + 2], out[k + 3], in[k], in[k + 1], in[k + 2], in[k + 3],
+                           in[H + k], in[H + k + 1], in[H + k + 2], in[H + k + 3]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < H; ++k) pair_reduce1<FULL>(out[k], in[k], in[H + k]);
+    }
+  }
+}
+
+// Same halving across lane pairs (i, i ^ 2) or (i, i ^ 1); `upper` tells whether this lane is
+// the one of its pair that keeps the upper half.
+template <int CTRL, int CNT>
+__device__ __forceinline__ void level_quad(const float (&in)[CNT], float (&out)[half_or_one(CNT)], bool upper) {
+  if constexpr (CNT == 1) {
+    out[0] = dpp_add<CTRL>(in[0]);
+  } else {
+    constexpr int H = CNT / 2;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+      const float lo = dpp_add<CTRL>(in[k]);
+      const float hi = dpp_add<CTRL>(in[H + k]);
+      out[k] = upper ? hi : lo;
+    }
+  }
+}
+
+// Sums x[n] over the LPR lanes of a token row.  With N >= LPR values per lane, lane c of the
+// row ends with the N/LPR complete sums of indices c*N/LPR ...; with fewer, index c / (LPR/N)
+// is replicated over LPR/N neighbouring lanes.
+template <int LPR, int N>
+__device__ __forceinline__ void row_reduce_scatter(const float (&x)[N], float (&y)[(N >= LPR) ? N / LPR : 1], int lane) {
+  constexpr int C1 = (LPR == 16) ? half_or_one(N) : N;
+  constexpr int C2 = half_or_one(C1);
+  constexpr int C3 = half_or_one(C2);
+  constexpr int C4 = half_or_one(C3);
+  static_assert(C4 == ((N >= LPR) ? N / LPR : 1), "level sizes");
+  float a[C1], b[C2], c[C3];
+  if constexpr (LPR == 16) {
+    level_mirror<true, N>(x, a);
+  } else {
+#pragma unroll
+    for (int k = 0; k < N; ++k) a[k] = x[k];
+  }
+  level_mirror<false, C1>(a, b);
+  level_quad<kDppXor2, C2>(b, c, (lane & 2) != 0);
+  level_quad<kDppXor1, C3>(c, y, (lane & 1) != 0);
+}
+
+__device__ __forceinline__ float same_head_max(float x) {
+#pragma unroll
+  for (int off = kSameHeadStride; off < 64; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+__device__ __forceinline__ float same_head_sum(float x) {
+#pragma unroll
+  for (int off = kSameHeadStride; off < 64; off <<= 1) x += __shfl_xor(x, off, 64);
   return x;
 }
 
@@ -67,16 +193,13 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
 
-__device__ __forceinline__ float dot8(const u32x4& a, const u32x4& b) {
-  float s = dot2(a.x, b.x, 0.0f);
+__device__ __forceinline__ float dot8(const u32x4& a, const u32x4& b, float s) {
+  s = dot2(a.x, b.x, s);
   s = dot2(a.y, b.y, s);
   s = dot2(a.z, b.z, s);
   s = dot2(a.w, b.w, s);
   return s;
 }
-
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -88,17 +211,26 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // G: query heads per kv head.  D: head dim.  PF: KV blocks kept in flight per wave.
 template <int G, int D, int PF>
 __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(DecodeLaunch a) {
-  constexpr int LPR = D / 8;          // lanes per token row
-  constexpr int TPI = 64 / LPR;       // token rows per wave load instruction
-  constexpr int NI = kBlockTokens / TPI;  // load instructions per K (or V) tile of one block
+  constexpr int LPR = D / 8;                // lanes per K row
+  constexpr int TPI = 64 / LPR;             // K rows (tokens) per wave load instruction
+  constexpr int NI = kBlockTokens / TPI;    // load instructions per K tile (and per V tile)
+  constexpr int N = G * NI;                 // partial logits per lane and block
+  constexpr int VPL = (N >= LPR) ? N / LPR : 1;   // complete logits per lane after the reduce
+  constexpr int REP = (N >= LPR) ? 1 : LPR / N;   // lanes that share one logit otherwise
   constexpr int kTileElems = kBlockTokens * D;
+  static_assert(LPR / NI == kSameHeadStride, "lanes that share a head are 4 apart");
 
   const int item = blockIdx.x / a.n_kv_heads;
   const int h = blockIdx.x - item * a.n_kv_heads;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int r = lane / LPR;           // token row within a load instruction
-  const int c = lane - r * LPR;       // 8-element slice of the head dim
+  const int r = lane / LPR;                 // K: token row within a load instruction
+  const int c = lane - r * LPR;             // K: 8-element slice of the head dim
+  const int half = lane & 1;                // V: which 8 of the block's 16 tokens
+  // (token, head) of this lane's complete logits: index n = i*G + g over (load i, head g)
+  const int n0 = (N >= LPR) ? c * VPL : c / REP;
+  const int my_tok = (n0 / G) * TPI + r;    // token within the block
+  const int my_g0 = n0 % G;                 // first (or only) head; the second is my_g0 + 1
 
   const int b = a.item_b[item];
   const int blk_begin = a.item_blk_begin[item];
@@ -117,26 +249,32 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
   typedef const __attribute__((address_space(4))) int32_t* const_ids_t;
   const const_ids_t wave_ids = (const_ids_t)(reinterpret_cast<uintptr_t>(table + w_begin));
 
+  __shared__ __attribute__((aligned(16))) uint16_t s_p[kWavesPerGroup][G][kBlockTokens];
+  __shared__ float s_f[kWavesPerGroup][3][G];
+  __shared__ float s_acc[kWavesPerGroup][G][D];
+
   u32x4 qreg[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const uint16_t* qp = a.q + (static_cast<int64_t>(b) * a.n_q_heads + h * G + g) * D + c * 8;
     qreg[g] = *reinterpret_cast<const u32x4*>(qp);
   }
-
   // Pin the query registers here: otherwise their loads are still counted as pending at
   // the head of the main loop and every iteration drains the whole load queue for them.
 #pragma unroll
   for (int g = 0; g < G; ++g) asm volatile("" : "+v"(qreg[g]));
 
-  float m_ref[G], l_sum[G], acc[G][8];
+  float m_ref[VPL], l_exact[VPL], l_round[VPL], acc[G][NI];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m_ref[g] = -INFINITY;
-    l_sum[g] = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[g][e] = 0.0f;
+  for (int v = 0; v < VPL; ++v) {
+    m_ref[v] = -INFINITY;
+    l_exact[v] = 0.0f;
+    l_round[v] = 0.0f;
   }
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int i = 0; i < NI; ++i) acc[g][i] = 0.0f;
 
   // Physical block ids travel through the scalar cache, one ring entry per pipeline stage,
   // each fetched a full round (PF blocks) before the loads that need it are issued.
@@ -147,8 +285,8 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
   u32x4 kreg[PF][NI], vreg[PF][NI];
   const int64_t head_stride = 2 * kTileElems;
   const int64_t block_stride = static_cast<int64_t>(a.n_kv_heads) * head_stride;
-  const int lane_elem_k = r * D + c * 8;
-  const int lane_elem_v = lane_elem_k + kTileElems;
+  const int lane_elem_k = r * D + c * 8;           // K tile [16][D]
+  const int lane_elem_v = kTileElems + lane * 8;   // V tile [D][16]: row lane/2 (+32 per load), tokens half*8..
 
   auto issue = [&](int stage, int j) {
     const int phys = id_ring[stage];
@@ -159,71 +297,78 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
       kreg[stage][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + i * TPI * D + lane_elem_k));
 #pragma unroll
     for (int i = 0; i < NI; ++i)
-      vreg[stage][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + i * TPI * D + lane_elem_v));
+      vreg[stage][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + i * 512 + lane_elem_v));
   };
 
   auto compute = [&](int stage, int j) {
-    const int tok0 = (w_begin + j) * kBlockTokens;
-    const int n_valid = len - tok0;                  // >= 1; < 16 only in a trajectory's last block
-    float z[G][NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      float part[G];
-#pragma unroll
-      for (int g = 0; g < G; ++g) part[g] = dot8(qreg[g], kreg[stage][i]);
-      row_sum<LPR, G>(part);
-#pragma unroll
-      for (int g = 0; g < G; ++g) z[g][i] = part[g] * a.scale_log2;
-    }
+    const int n_valid = len - (w_begin + j) * kBlockTokens;   // >= 1; < 16 only in the last block
 
-    if (n_valid < kBlockTokens) {                    // wave-uniform: ragged tail of the context
+    // ---- logits: partial dots, then reduce-scatter over the lanes of each K row
+    float part[N];
 #pragma unroll
-      for (int i = 0; i < NI; ++i) {
-        const bool dead = i * TPI + r >= n_valid;
-        if (dead) {
-          vreg[stage][i] = u32x4{0u, 0u, 0u, 0u};     // slots past the length may hold NaN
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-          for (int g = 0; g < G; ++g) z[g][i] = -INFINITY;
-        }
-      }
-    }
+      for (int g = 0; g < G; ++g) part[i * G + g] = dot8(qreg[g], kreg[stage][i], 0.0f);
+    float z[VPL];
+    row_reduce_scatter<LPR, N>(part, z, lane);
+    const bool dead = my_tok >= n_valid;            // slots past the length may hold anything
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) z[v] = dead ? -INFINITY : z[v] * a.scale_log2;
 
+    // ---- lazily moved reference maximum
     bool grow = false;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float zmax = z[g][0];
+    for (int v = 0; v < VPL; ++v) grow |= z[v] > m_ref[v] + kLazyMaxSlack;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
 #pragma unroll
-      for (int i = 1; i < NI; ++i) zmax = fmaxf(zmax, z[g][i]);
-      grow |= zmax > m_ref[g] + kLazyMaxSlack;
-    }
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {    // rare: move the reference maximum
+      for (int v = 0; v < VPL; ++v) {
+        const float m_new = fmaxf(m_ref[v], same_head_max(z[v]));
+        const float shrink = __builtin_amdgcn_exp2f(m_ref[v] - m_new);
+        l_exact[v] *= shrink;
+        l_round[v] *= shrink;
+        m_ref[v] = m_new;
+        if (lane < kSameHeadStride) s_f[wave][0][my_g0 + v] = shrink;
+      }
+      wave_lds_fence();
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float zmax = z[g][0];
+        const float shrink = s_f[wave][0][g];
 #pragma unroll
-        for (int i = 1; i < NI; ++i) zmax = fmaxf(zmax, z[g][i]);
-        const float m_new = fmaxf(m_ref[g], wave_max(zmax));
-        const float shrink = __builtin_amdgcn_exp2f(m_ref[g] - m_new);
-        l_sum[g] *= shrink;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] *= shrink;
-        m_ref[g] = m_new;
+        for (int i = 0; i < NI; ++i) acc[g][i] *= shrink;
       }
     }
 
+    // ---- p, rounded to bf16, to the wave's LDS row of its head
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const u32x4 vv = vreg[stage][i];
-      const float v[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                          bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+    for (int v = 0; v < VPL; ++v) {
+      const float p = __builtin_amdgcn_exp2f(z[v] - m_ref[v]);
+      const uint16_t pb = f32_to_bf16_rne(p);
+      l_exact[v] += p;
+      l_round[v] += __builtin_bit_cast(float, static_cast<uint32_t>(pb) << 16);
+      s_p[wave][my_g0 + v][my_tok] = pb;
+    }
+    wave_lds_fence();
+
+    // ---- V: 8 tokens of one head-dim element per lane and load
+    if (n_valid < kBlockTokens) {                    // wave-uniform: zero the dead tokens' columns
+      const int nv = n_valid - half * 8;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = __builtin_amdgcn_exp2f(z[g][i] - m_ref[g]);
-        l_sum[g] += p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, v[e], acc[g][e]);
+      for (int i = 0; i < NI; ++i) {
+        u32x4 vv = vreg[stage][i];
+        vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
+        vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
+        vv.z &= (4 < nv ? 0x0000ffffu : 0u) | (5 < nv ? 0xffff0000u : 0u);
+        vv.w &= (6 < nv ? 0x0000ffffu : 0u) | (7 < nv ? 0xffff0000u : 0u);
+        vreg[stage][i] = vv;
       }
     }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const u32x4 pp = *reinterpret_cast<const u32x4*>(&s_p[wave][g][half * 8]);
+#pragma unroll
+      for (int i = 0; i < NI; ++i) acc[g][i] = dot8(pp, vreg[stage][i], acc[g][i]);
+    }
+    wave_lds_fence();
   };
 
   // The steady-state loop is entered only behind an unconditional prologue: the compiler
@@ -258,51 +403,55 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
     }
   }
 
-  // ---- merge the TPI token rows of the wave (lanes with equal c) ----
+  // ---- wave totals: the two token halves of each head-dim element sit in lanes l, l ^ 1;
+  //      the softmax sums of a head are spread over the lanes that carry that head
 #pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
+  for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      l_sum[g] += __shfl_xor(l_sum[g], off, 64);
+    for (int i = 0; i < NI; ++i) acc[g][i] = dpp_add<kDppXor1>(acc[g][i]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] += __shfl_xor(acc[g][e], off, 64);
-    }
+  for (int v = 0; v < VPL; ++v) {
+    l_exact[v] = same_head_sum(l_exact[v]);
+    l_round[v] = same_head_sum(l_round[v]);
   }
 
-  // ---- merge the four waves through LDS and store the item's partial result ----
-  __shared__ float s_acc[kWavesPerGroup][G][D];
-  __shared__ float s_m[kWavesPerGroup][G];
-  __shared__ float s_l[kWavesPerGroup][G];
-  if (r == 0) {
+  // ---- merge the four waves through LDS and store the item's partial result
+  wave_lds_fence();
+  if (half == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s_acc[wave][g][c * 8 + e] = acc[g][e];
-      if (c == 0) {
-        s_m[wave][g] = m_ref[g];
-        s_l[wave][g] = l_sum[g];     // each row lane holds the same sum; rows were added above
-      }
+      for (int i = 0; i < NI; ++i) s_acc[wave][g][i * 32 + (lane >> 1)] = acc[g][i];
+  }
+  if (lane < kSameHeadStride) {
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      s_f[wave][0][my_g0 + v] = m_ref[v];
+      s_f[wave][1][my_g0 + v] = l_round[v];
+      s_f[wave][2][my_g0 + v] = l_exact[v];
     }
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerGroup * 64) {
     const int g = idx / D;
     const int e = idx - g * D;
-    float M = s_m[0][g];
+    float M = s_f[0][0][g];
 #pragma unroll
-    for (int w = 1; w < kWavesPerGroup; ++w) M = fmaxf(M, s_m[w][g]);
-    float val = 0.0f, L = 0.0f;
+    for (int w = 1; w < kWavesPerGroup; ++w) M = fmaxf(M, s_f[w][0][g]);
+    float val = 0.0f, Lr = 0.0f, Le = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWavesPerGroup; ++w) {
-      const float f = __builtin_amdgcn_exp2f(s_m[w][g] - M);   // 0 for a wave that had no block
+      const float f = __builtin_amdgcn_exp2f(s_f[w][0][g] - M);   // 0 for a wave that had no block
       val = fmaf(f, s_acc[w][g][e], val);
-      L = fmaf(f, s_l[w][g], L);
+      Lr = fmaf(f, s_f[w][1][g], Lr);
+      Le = fmaf(f, s_f[w][2][g], Le);
     }
     const int64_t pj = static_cast<int64_t>(slot) * a.n_q_heads + h * G + g;
     a.part_acc[pj * D + e] = val;
     if (e == 0) {
-      a.part_ml[pj * 2 + 0] = M;
-      a.part_ml[pj * 2 + 1] = L;
+      a.part_ml[pj * 4 + 0] = M;
+      a.part_ml[pj * 4 + 1] = Lr;
+      a.part_ml[pj * 4 + 2] = Le;
     }
   }
 }
@@ -316,17 +465,18 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeLaunch a) {
   const int p0 = a.part_off[b];
   const int ns = a.nsplit[b];
   float M = -INFINITY;
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 2]);
-  float num = 0.0f, den = 0.0f;
+  for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 4]);
+  float num = 0.0f, den = 0.0f, den_exact = 0.0f;
   for (int s = 0; s < ns; ++s) {
     const int64_t pj = static_cast<int64_t>(p0 + s) * a.n_q_heads + j;
-    const float f = __builtin_amdgcn_exp2f(a.part_ml[pj * 2] - M);
-    den = fmaf(f, a.part_ml[pj * 2 + 1], den);
+    const float f = __builtin_amdgcn_exp2f(a.part_ml[pj * 4] - M);
+    den = fmaf(f, a.part_ml[pj * 4 + 1], den);
+    den_exact = fmaf(f, a.part_ml[pj * 4 + 2], den_exact);
     num = fmaf(f, a.part_acc[pj * D + e], num);
   }
   const int64_t oj = static_cast<int64_t>(b) * a.n_q_heads + j;
   a.out[oj * D + e] = f32_to_bf16_rne(num / den);
-  if (a.lse != nullptr && e == 0) a.lse[oj] = (M + __builtin_log2f(den)) * 0.6931471805599453f;
+  if (a.lse != nullptr && e == 0) a.lse[oj] = (M + __builtin_log2f(den_exact)) * 0.6931471805599453f;
 }
 
 template <int G, int D, int PF>
@@ -349,14 +499,14 @@ hipError_t launch_decode_splitk(const DecodeLaunch& a, hipStream_t stream) {
       case 1: return launch_splitk<1, 128, 3>(a, stream);
       case 2: return launch_splitk<2, 128, 3>(a, stream);
       case 4: return launch_splitk<4, 128, 3>(a, stream);
-      case 8: return launch_splitk<8, 128, 2>(a, stream);
+      case 8: return launch_splitk<8, 128, 3>(a, stream);
     }
   } else if (a.head_dim == 64) {
     switch (G) {
       case 1: return launch_splitk<1, 64, 3>(a, stream);
       case 2: return launch_splitk<2, 64, 3>(a, stream);
       case 4: return launch_splitk<4, 64, 3>(a, stream);
-      case 8: return launch_splitk<8, 64, 2>(a, stream);
+      case 8: return launch_splitk<8, 64, 3>(a, stream);
     }
   }
   return hipErrorInvalidValue;

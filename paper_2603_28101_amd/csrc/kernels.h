@@ -8,7 +8,7 @@ namespace heddle {
 
 // Arguments of the split-K decode pass.  All pointers are device memory.
 struct DecodeLaunch {
-  const uint16_t* pool;        // bf16 [n_blocks][n_kv][2][16][d]
+  const uint16_t* pool;        // bf16 [n_blocks][n_kv]{K tile [16][d], V tile [d][16]}
   const int32_t* row_off;      // [B+1]
   const int32_t* block_ids;    // CSR block table
   const int32_t* lens;         // [B]
@@ -20,7 +20,8 @@ struct DecodeLaunch {
   const int32_t* nsplit;       // [B]
   const uint16_t* q;           // bf16 [B][n_q][d]
   float* part_acc;             // f32 [n_parts][n_q][d]   unnormalised sum of p * v
-  float* part_ml;              // f32 [n_parts][n_q][2]   (max logit in log2 units, sum of p)
+  float* part_ml;              // f32 [n_parts][n_q][4]   (max logit in log2 units, sum of bf16-rounded p,
+                               //                          sum of unrounded p, unused)
   uint16_t* out;               // bf16 [B][n_q][d]
   float* lse;                  // f32 [B][n_q] or nullptr
   int32_t B, n_items, n_q_heads, n_kv_heads, head_dim;

@@ -8,7 +8,9 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// One workgroup per new token row; thread t moves one 16-byte piece of K and of V.
+// One workgroup per new token row; thread t moves one 8-element piece of K (one 16-byte
+// store into the token-major K tile) and of V (eight 2-byte stores into the transposed V
+// tile, where the 16 tokens of a head-dim element are contiguous).
 // Row i of trajectory b (rows cu_rows[b] .. cu_rows[b+1]) goes to position first_pos[b] + i.
 __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
   const int row = blockIdx.x;
@@ -22,16 +24,23 @@ __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
   const int pos = a.first_pos[b] + (row - a.cu_rows[b]);
   const int phys = a.block_ids[a.row_off[b] + pos / 16];
   const int slot = pos % 16;
-  const int pieces_per_head = a.head_dim / 8;
+  const int D = a.head_dim;
+  const int pieces_per_head = D / 8;
   const int n_pieces = a.n_kv_heads * pieces_per_head;
   for (int t = threadIdx.x; t < n_pieces; t += blockDim.x) {
     const int h = t / pieces_per_head;
     const int c = t - h * pieces_per_head;
-    const int64_t src = (static_cast<int64_t>(row) * a.n_kv_heads + h) * a.head_dim + c * 8;
-    const int64_t dst_k = ((static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 + slot) * a.head_dim + c * 8;
-    const int64_t dst_v = dst_k + 16 * a.head_dim;
-    *reinterpret_cast<u32x4*>(a.pool + dst_k) = *reinterpret_cast<const u32x4*>(a.k + src);
-    *reinterpret_cast<u32x4*>(a.pool + dst_v) = *reinterpret_cast<const u32x4*>(a.v + src);
+    const int64_t src = (static_cast<int64_t>(row) * a.n_kv_heads + h) * D + c * 8;
+    const int64_t tile_k = (static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 * D;
+    const int64_t tile_v = tile_k + 16 * D;
+    *reinterpret_cast<u32x4*>(a.pool + tile_k + slot * D + c * 8) = *reinterpret_cast<const u32x4*>(a.k + src);
+    const u32x4 vv = *reinterpret_cast<const u32x4*>(a.v + src);
+    const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint16_t x = static_cast<uint16_t>(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xffffu);
+      a.pool[tile_v + static_cast<int64_t>(c * 8 + e) * 16 + slot] = x;
+    }
   }
 }
 

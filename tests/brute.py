@@ -23,12 +23,15 @@ def softmax_attention(q, K, V, scale):
 
 
 def dense_from_pool(pool, row_off, block_ids, b, length, h):
-    """Token-ordered K, V lists of kv head h, element by element (no slicing
-    tricks): position p lives in block block_ids[row_off[b] + p // 16], slot p % 16."""
-    d = pool.shape[4]
+    """Token-ordered K, V lists of kv head h, element by element with flat offsets (no
+    reshapes): position p lives in block block_ids[row_off[b] + p // 16], slot p % 16;
+    element c of its K row is at [blk][h][0][slot*d + c], of its V row at [blk][h][1][c*16 + slot]
+    (the V tile is stored transposed)."""
+    d = pool.shape[3] // 16
     K, V = [], []
     for p in range(length):
         blk = int(block_ids[int(row_off[b]) + p // 16])
-        K.append([bf16_to_float(pool[blk, h, 0, p % 16, c]) for c in range(d)])
-        V.append([bf16_to_float(pool[blk, h, 1, p % 16, c]) for c in range(d)])
+        slot = p % 16
+        K.append([bf16_to_float(pool[blk, h, 0, slot * d + c]) for c in range(d)])
+        V.append([bf16_to_float(pool[blk, h, 1, c * 16 + slot]) for c in range(d)])
     return K, V

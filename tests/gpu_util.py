@@ -5,9 +5,17 @@ from __future__ import annotations
 import numpy as np
 
 ATOL, RTOL = 1e-2, 1e-2          # the stated parity bound: |err| <= 1e-2 + 1e-2 |ref|
-# what a correct fp32-accumulate / bf16-output kernel actually achieves: half an ulp of bf16
-# (2^-9 relative) on the output plus a small absolute term from fp32 accumulation
-TIGHT_ATOL, TIGHT_RTOL = 3e-4, 4e-3
+# What a correct kernel achieves is far tighter, and the tests hold it to that as well:
+#   * the output is rounded to bf16 (8 significant bits): half an ulp, at most 2^-8 relative;
+#   * the softmax weights enter P.V rounded to bf16 (numerator and denominator alike): each
+#     weight carries an independent relative error, uniform in +-2^-9, standard deviation
+#     2^-9/sqrt(3); to first order the output moves by sum_t w_t delta_t (v_t - out), whose
+#     standard deviation is (2^-9/sqrt 3) * spread with spread = sqrt(sum w_t^2 (v_t-out)^2)
+#     (computed by the oracle); 8 standard deviations are allowed;
+#   * fp32 accumulation: a small absolute term.
+OUT_ULP = 2.0 ** -8
+P_SIGMA = 2.0 ** -9 / 3 ** 0.5
+TIGHT_ATOL = 5e-5
 LSE_ATOL = 1e-3
 
 
@@ -73,17 +81,18 @@ class DeviceCase:
         return bf16_to_host_bits(self.pool)
 
 
-def assert_close(got, ref, what="", tight=True):
+def assert_close(got, ref, what="", spread=None):
     got, ref = np.asarray(got), np.asarray(ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
     err = np.abs(got - ref)
     bound = ATOL + RTOL * np.abs(ref)
     worst = np.unravel_index(np.argmax(err - bound), err.shape)
     assert (err <= bound).all(), f"{what}: |err|={err[worst]:.3e} at {worst}, ref={ref[worst]:.4e}"
-    if tight:
-        tb = TIGHT_ATOL + TIGHT_RTOL * np.abs(ref)
+    if spread is not None:
+        tb = TIGHT_ATOL + 1.01 * OUT_ULP * np.abs(ref) + 8 * P_SIGMA * np.asarray(spread)
         worst = np.unravel_index(np.argmax(err - tb), err.shape)
-        assert (err <= tb).all(), f"{what} (tight): |err|={err[worst]:.3e} at {worst}, ref={ref[worst]:.4e}"
+        assert (err <= tb).all(), (f"{what} (derived bound): |err|={err[worst]:.3e} > {tb[worst]:.3e} at {worst}, "
+                                   f"ref={ref[worst]:.4e}")
 
 
 def assert_lse_close(got, ref, what=""):

@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 
 
 def oracle_decode(c, lens=None, pool=None):
+    """(out, lse, spread) of the float64 oracle."""
     return oa.decode(c["pool"] if pool is None else pool, c["row_off"], c["block_ids"],
-                     c["lens"] if lens is None else lens, c["q"], c["n_kv_heads"])
+                     c["lens"] if lens is None else lens, c["q"], c["n_kv_heads"], with_spread=True)
 
 
 def small(seed, lens, n_q, n_kv, d, **kw):
@@ -27,8 +28,8 @@ def test_tiny_workload(seed):
     c = hw.make_workload(1, seed)
     print("tiny decode seed", seed, "lens", c["lens"].tolist(), flush=True)
     out, lse = DeviceCase(c).decode()
-    ref, ref_lse = oracle_decode(c)
-    assert_close(out, ref, "tiny out")
+    ref, ref_lse, spread = oracle_decode(c)
+    assert_close(out, ref, "tiny out", spread)
     assert_lse_close(lse, ref_lse, "tiny lse")
 
 
@@ -40,12 +41,12 @@ RAGGED = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 255, 256, 257, 1000, 10
 def test_ragged_lengths_all_head_shapes(n_q, n_kv, d):
     c = small(10, RAGGED, n_q, n_kv, d)
     print("ragged", n_q, n_kv, d, flush=True)
-    ref, ref_lse = oracle_decode(c)
+    ref, ref_lse, spread = oracle_decode(c)
     # default plan (mostly unsplit) and a plan forced into many small splits
     for kw in (dict(), dict(n_cu=64, wg_per_cu=8, min_chunk_blk=1, tile_blk=1, max_split=64),
                dict(n_cu=8, wg_per_cu=1, min_chunk_blk=4, tile_blk=4, max_split=3)):
         out, lse = DeviceCase(c, **kw).decode()
-        assert_close(out, ref, f"ragged {kw}")
+        assert_close(out, ref, f"ragged {kw}", spread)
         assert_lse_close(lse, ref_lse, f"ragged lse {kw}")
 
 
@@ -54,7 +55,8 @@ def test_lse_output_is_optional():
     dc = DeviceCase(c)
     out, lse = dc.decode(want_lse=False)
     assert np.isnan(lse).all()
-    assert_close(out, oracle_decode(c)[0])
+    ref, _, spread = oracle_decode(c)
+    assert_close(out, ref, "no lse", spread)
 
 
 def test_needle_at_every_split_and_wave_boundary():
@@ -86,14 +88,14 @@ def test_needle_at_every_split_and_wave_boundary():
         blk = base["block_ids"][pos // 16]
         for h in range(n_kv):
             qv = bits_to_f64(base["q"][0, h * G])
-            c["pool"][blk, h, 0, pos % 16] = hw.f32_to_bf16_bits((40.0 * math.sqrt(d) * qv / (qv @ qv)).astype(np.float32))
+            hw.k_view(c["pool"])[blk, h, pos % 16] = hw.f32_to_bf16_bits((40.0 * math.sqrt(d) * qv / (qv @ qv)).astype(np.float32))
             marker = np.zeros(d, dtype=np.float32)
             marker[(pos + h) % d] = 1000.0
-            c["pool"][blk, h, 1, pos % 16] = hw.f32_to_bf16_bits(marker)
+            hw.v_view(c["pool"])[blk, h, :, pos % 16] = hw.f32_to_bf16_bits(marker)
         dc.pool.copy_(to_dev_bf16(c["pool"]))
         out, lse = dc.decode()
-        ref, ref_lse = oracle_decode(c)
-        assert_close(out, ref, f"needle at {pos}")
+        ref, ref_lse, spread = oracle_decode(c)
+        assert_close(out, ref, f"needle at {pos}", spread)
         assert_lse_close(lse, ref_lse, f"needle lse at {pos}")
         for j in range(n_q):
             assert abs(out[0, j, (pos + j // G) % d] - 1000.0) < 8.0, (pos, j)
@@ -133,8 +135,8 @@ def test_new_row_is_stored_then_attended():
     for b in range(5):
         oa.write_kv(pool, c["row_off"], c["block_ids"], [lens[b] - 1], b, k_new[b:b + 1], v_new[b:b + 1])
     assert np.array_equal(dc.pool_bits(), pool)          # exactly those rows changed, bit for bit
-    ref, ref_lse = oracle_decode(c, pool=pool)
-    assert_close(out, ref, "decode with new row")
+    ref, ref_lse, spread = oracle_decode(c, pool=pool)
+    assert_close(out, ref, "decode with new row", spread)
     assert_lse_close(lse, ref_lse)
 
 
@@ -159,15 +161,16 @@ def test_back_to_back_calls_share_scratch_safely():
     big = small(17, [5000, 4000, 3000, 100], 8, 2, 128)
     tiny = small(18, [3, 50], 8, 2, 128)
     d_big, d_tiny = DeviceCase(big), DeviceCase(tiny)
-    ref_big, _ = oracle_decode(big)
-    ref_tiny, _ = oracle_decode(tiny)
+    ref_big, _, sp_big = oracle_decode(big)
+    ref_tiny, _, sp_tiny = oracle_decode(tiny)
     for _ in range(3):
-        assert_close(d_big.decode()[0], ref_big)
-        assert_close(d_tiny.decode()[0], ref_tiny)
+        assert_close(d_big.decode()[0], ref_big, "big", sp_big)
+        assert_close(d_tiny.decode()[0], ref_tiny, "tiny", sp_tiny)
     # same context, shrinking then growing batch
     out_small, _ = d_big.decode(lens=[17, 1, 1, 1])
-    assert_close(out_small, oracle_decode(big, lens=[17, 1, 1, 1])[0])
-    assert_close(d_big.decode()[0], ref_big)
+    ref_small, _, sp_small = oracle_decode(big, lens=[17, 1, 1, 1])
+    assert_close(out_small, ref_small, "shrunk batch", sp_small)
+    assert_close(d_big.decode()[0], ref_big, "big again", sp_big)
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4])
@@ -186,10 +189,11 @@ def test_full_size_workloads_sampled(cfg):
     picks = {int(order[-1]), int(order[-2]), int(order[0]), int(order[len(order) // 2])}
     picks |= set(int(x) for x in rng.choice(len(lens), 4, replace=False))
     pairs = [(b, int(j)) for b in sorted(picks) for j in rng.choice(w.n_q_heads, 3, replace=False)]
-    ref, ref_lse = oa.decode_rows(c["pool"], c["row_off"], c["block_ids"], lens, c["q"], w.n_kv_heads, pairs)
+    ref, ref_lse, spread = oa.decode_rows(c["pool"], c["row_off"], c["block_ids"], lens, c["q"], w.n_kv_heads,
+                                          pairs, with_spread=True)
     got = np.array([out[b, j] for b, j in pairs])
     got_lse = np.array([lse[b, j] for b, j in pairs])
-    assert_close(got, ref, f"workload {cfg}")
+    assert_close(got, ref, f"workload {cfg}", spread)
     assert_lse_close(got_lse, ref_lse, f"workload {cfg} lse")
     # property that holds at any size: sum_t w_t = 1, so |out| never exceeds max |V| (~6 for N(0,1) draws)
     assert np.abs(out).max() < 8.0

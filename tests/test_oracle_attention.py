@@ -65,7 +65,7 @@ def test_gqa_mapping_is_contiguous_groups():
     c = small_case(3, [20], poison=False)
     pool = c["pool"]
     pool[:, 1, 0] = 0
-    pool[:, 1, 1] = bits(7.0)
+    pool[:, 1, 1] = bits(7.0)      # every V element of kv head 1
     out, lse = run_decode(c)
     assert np.allclose(out[0, 2:], 7.0) and np.allclose(lse[0, 2:], math.log(20))
     assert not np.allclose(out[0, :2], 7.0)
@@ -78,8 +78,8 @@ def test_len_one_returns_v_and_logit():
     for b in range(3):
         blk = c["block_ids"][c["row_off"][b]]
         for j in range(4):
-            v0 = oa.bf16_bits_to_f64(c["pool"][blk, j // 2, 1, 0])
-            k0 = oa.bf16_bits_to_f64(c["pool"][blk, j // 2, 0, 0])
+            v0 = oa.bf16_bits_to_f64(hw.v_view(c["pool"])[blk, j // 2, :, 0])
+            k0 = oa.bf16_bits_to_f64(hw.k_view(c["pool"])[blk, j // 2, 0])
             assert np.array_equal(out[b, j], v0)
             assert abs(lse[b, j] - s * float(oa.bf16_bits_to_f64(c["q"][b, j]) @ k0)) < 1e-13
 
@@ -88,8 +88,8 @@ def test_identical_keys_give_mean_of_values():
     n = 37
     c = small_case(5, [n], poison=False)
     row = c["block_ids"][: c["row_off"][1]]
-    key = c["pool"][row[0], :, 0, 0].copy()         # [n_kv][d]
-    c["pool"][row, :, 0] = key[None, :, None, :]
+    key = hw.k_view(c["pool"])[row[0], :, 0].copy()         # [n_kv][d]
+    hw.k_view(c["pool"])[row] = key[None, :, None, :]
     out, lse = run_decode(c)
     K, V = oa.gather(c["pool"], c["row_off"], c["block_ids"], 0, n)
     s = 1 / math.sqrt(c["head_dim"])
@@ -102,7 +102,7 @@ def test_identical_keys_give_mean_of_values():
 def test_constant_values_are_returned():
     c = small_case(6, [50, 3], poison=False)
     const = bits(np.linspace(-2, 2, 8))
-    c["pool"][:, :, 1] = const
+    hw.v_view(c["pool"])[:] = const[None, None, :, None]
     out, _ = run_decode(c)
     assert np.allclose(out, oa.bf16_bits_to_f64(const), rtol=1e-14, atol=1e-15)
 
@@ -137,10 +137,10 @@ def needle_case(seed, lens, b, pos, n_q=4, n_kv=2, d=8):
         # all q heads of the group must agree: make them identical first
         c["q"][b, h * G:(h + 1) * G] = c["q"][b, h * G]
         qv = oa.bf16_bits_to_f64(c["q"][b, h * G])
-        c["pool"][blk, h, 0, pos % 16] = bits(40.0 * math.sqrt(d) * qv / (qv @ qv))   # logit = 40
+        hw.k_view(c["pool"])[blk, h, pos % 16] = bits(40.0 * math.sqrt(d) * qv / (qv @ qv))   # logit = 40
         marker = np.zeros(d, dtype=np.float32)
         marker[(pos + h) % d] = 1000.0
-        c["pool"][blk, h, 1, pos % 16] = bits(marker)
+        hw.v_view(c["pool"])[blk, h, :, pos % 16] = bits(marker)
     return c
 
 
@@ -267,10 +267,12 @@ def test_append_writes_exactly_the_chunk_slots():
             blk = c["block_ids"][c["row_off"][b] + p // 16]
             r = c["cu_chunk"][b] + i
             for h in range(2):
-                expect[blk, h, 0, p % 16] = c["k_new"][r, h]
-                expect[blk, h, 1, p % 16] = c["v_new"][r, h]
+                d = c["head_dim"]
+                for e in range(d):
+                    expect[blk, h, 0, (p % 16) * d + e] = c["k_new"][r, h, e]
+                    expect[blk, h, 1, e * 16 + p % 16] = c["v_new"][r, h, e]
     assert np.array_equal(pool_after, expect)
-    changed = np.nonzero((pool_after != c["pool"]).any(axis=(1, 2, 3, 4)))[0]
+    changed = np.nonzero((pool_after != c["pool"]).any(axis=(1, 2, 3)))[0]
     referenced = set(int(x) for x in c["block_ids"])
     assert set(int(x) for x in changed) <= referenced
 
@@ -313,3 +315,26 @@ def test_pack_unpack_round_trip():
     ids2[:3] = dst
     K2, V2 = oa.gather(pool2, c["row_off"], ids2, 0, 40)
     assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
+
+
+def test_weight_spread_matches_direct_perturbation():
+    """weight_spread is the first-order standard deviation of the output under independent
+    relative perturbations of the weights; check it against an explicit finite perturbation."""
+    rng = np.random.default_rng(0)
+    n, d = 23, 5
+    w = rng.random(n)
+    w /= w.sum()
+    V = rng.standard_normal((n, d))
+    out = w @ V
+    eps = 1e-6
+    # exact derivative of out wrt delta_t at 0: w_t (V_t - out); spread = sqrt(sum of squares)
+    J = np.zeros((n, d))
+    for t in range(n):
+        w2 = w.copy()
+        w2[t] *= 1 + eps
+        J[t] = ((w2 @ V) / w2.sum() - out) / eps
+    assert np.allclose(oa.weight_spread(w, V, out), np.sqrt((J ** 2).sum(axis=0)), rtol=1e-4)
+    # a single dominant token: the output cannot move
+    w1 = np.zeros(n)
+    w1[3] = 1.0
+    assert np.allclose(oa.weight_spread(w1, V, V[3]), 0.0)
