@@ -58,12 +58,14 @@ def attend(q, K, V, scale):
     return w @ V, m + math.log(denom), w
 
 
-def weight_spread(w, V, out):
-    """sqrt(sum_t w_t^2 (V[t] - out)^2) per output element: the standard deviation of the
-    output under independent unit-variance relative perturbations of the weights (first
-    order, numerator and denominator perturbed alike).  The tests use it to bound what
-    rounding the weights to bf16 may do to the result."""
-    return np.sqrt((w * w) @ ((V - out) ** 2))
+def weight_spread(w, V, out, centered=True):
+    """Standard deviation of the output under independent unit-variance relative
+    perturbations of the weights, to first order.  centered: numerator and denominator are
+    perturbed alike, sqrt(sum_t w_t^2 (V[t] - out)^2); otherwise only the numerator is,
+    sqrt(sum_t w_t^2 V[t]^2).  The tests use it to bound what rounding the weights to bf16
+    may do to a result."""
+    dev = V - out if centered else V
+    return np.sqrt((w * w) @ (dev ** 2))
 
 
 def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=None, with_spread=False):
@@ -196,7 +198,7 @@ def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_
             for j in range(n_q):
                 out[r, j], lse[r, j], w = attend(qr[j], K[j // G][:n_keys], V[j // G][:n_keys], s)
                 if with_spread:
-                    spread[r, j] = weight_spread(w, V[j // G][:n_keys], out[r, j])
+                    spread[r, j] = weight_spread(w, V[j // G][:n_keys], out[r, j], centered=False)
     return (out, lse, spread) if with_spread else (out, lse)
 
 

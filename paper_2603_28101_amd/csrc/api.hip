@@ -282,7 +282,7 @@ int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_
     const int64_t C = static_cast<int64_t>(cu_chunk_host[b + 1]) - cu_chunk_host[b];
     if (C < 1 || ctx_len_host[b] < 0 || ctx_len_host[b] + C > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
   }
-  if (tile_rows <= 0) tile_rows = 128 / (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads);
+  if (tile_rows <= 0) tile_rows = append_tile_rows(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads);
   if (tile_rows < 1) tile_rows = 1;
   std::vector<AppendTile> tiles;
   plan_append(B, ctx_len_host, cu_chunk_host, tile_rows, tiles);
@@ -416,9 +416,96 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
 }
 
 int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream) {
-  (void)hip_stream;
   if (ctx == nullptr || args == nullptr) return HEDDLE_E_INVAL;
-  return HEDDLE_E_UNSUPPORTED;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  const int32_t B = args->B;
+  if (B < 1 || !args->ctx_len_host || !args->cu_chunk_host || !args->row_off_host || !args->row_off ||
+      !args->block_ids || !args->q || !args->k || !args->v || !args->out)
+    return HEDDLE_E_INVAL;
+  if (args->cu_chunk_host[0] != 0 || args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t C = static_cast<int64_t>(args->cu_chunk_host[b + 1]) - args->cu_chunk_host[b];
+    const int64_t L = args->ctx_len_host[b];
+    if (C < 1 || L < 0 || L + C > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+    if (args->row_off_host[b + 1] < args->row_off_host[b] || !table_covers(args->row_off_host, b, L + C))
+      return HEDDLE_E_INVAL;
+  }
+  const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
+  if (!append_shape_supported(G, ctx->cfg.head_dim)) return HEDDLE_E_UNSUPPORTED;
+
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  plan_append(B, args->ctx_len_host, args->cu_chunk_host, append_tile_rows(G), ctx->tiles);
+  const size_t n_tiles = ctx->tiles.size();
+  const int32_t n_rows = args->cu_chunk_host[B];
+
+  // plan image: ctx_len[B] | cu_chunk[B+1] | 4 x tiles
+  const size_t words = 2 * static_cast<size_t>(B) + 1 + 4 * n_tiles;
+  StagingSlot* slot = nullptr;
+  int rc = acquire_slot(ctx, words, &slot);
+  if (rc != HEDDLE_OK) return rc;
+  int32_t* w = slot->host;
+  int32_t* h_len = w;
+  int32_t* h_cu = h_len + B;
+  int32_t* h_tb = h_cu + B + 1;
+  int32_t* h_tr0 = h_tb + n_tiles;
+  int32_t* h_trn = h_tr0 + n_tiles;
+  int32_t* h_tex = h_trn + n_tiles;
+  std::memcpy(h_len, args->ctx_len_host, sizeof(int32_t) * B);
+  std::memcpy(h_cu, args->cu_chunk_host, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
+  for (size_t i = 0; i < n_tiles; ++i) {
+    h_tb[i] = ctx->tiles[i].b;
+    h_tr0[i] = ctx->tiles[i].row0;
+    h_trn[i] = ctx->tiles[i].rows;
+    h_tex[i] = ctx->tiles[i].extent;
+  }
+  rc = upload(ctx, slot, words, stream);
+  if (rc != HEDDLE_OK) return rc;
+  ctx->enqueued = true;
+  const int32_t* d = ctx->dev_plan;
+
+  {
+    KvWriteLaunch kw{};
+    kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
+    kw.row_off = args->row_off;
+    kw.block_ids = args->block_ids;
+    kw.first_pos = d + (h_len - w);
+    kw.cu_rows = d + (h_cu - w);
+    kw.k = static_cast<const uint16_t*>(args->k);
+    kw.v = static_cast<const uint16_t*>(args->v);
+    kw.B = B;
+    kw.n_rows = n_rows;
+    kw.n_kv_heads = ctx->cfg.n_kv_heads;
+    kw.head_dim = ctx->cfg.head_dim;
+    TimedScope t(ctx, 3, stream);
+    HEDDLE_HIP(launch_kv_write(kw, stream));
+  }
+
+  AppendLaunch al{};
+  al.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
+  al.row_off = args->row_off;
+  al.block_ids = args->block_ids;
+  al.ctx_len = d + (h_len - w);
+  al.cu_chunk = d + (h_cu - w);
+  al.tile_b = d + (h_tb - w);
+  al.tile_row0 = d + (h_tr0 - w);
+  al.tile_rows_n = d + (h_trn - w);
+  al.tile_extent = d + (h_tex - w);
+  al.q = static_cast<const uint16_t*>(args->q);
+  al.out = static_cast<uint16_t*>(args->out);
+  al.lse = args->lse;
+  al.n_tiles = static_cast<int32_t>(n_tiles);
+  al.n_q_heads = ctx->cfg.n_q_heads;
+  al.n_kv_heads = ctx->cfg.n_kv_heads;
+  al.head_dim = ctx->cfg.head_dim;
+  al.scale_log2 = ctx->scale * 1.4426950408889634f;
+  {
+    TimedScope t(ctx, 2, stream);
+    HEDDLE_HIP(launch_append_attn(al, stream));
+  }
+  return HEDDLE_OK;
 }
 
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {

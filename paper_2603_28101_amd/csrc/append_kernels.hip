@@ -1,0 +1,274 @@
+// Causal chunked-append attention on the matrix cores (gfx950 MFMA).
+//
+// A tool-output chunk of C_b tokens is appended onto a trajectory's retained cache of L_b
+// tokens (paper Sec. 2.1: each step of a trajectory continues from the previous context;
+// Sec. 8 calls this tool-output prefill the dominant cost of prefill-heavy agents).  Chunk
+// row i sits at position L_b + i and attends to positions 0 .. L_b + i.  The chunk's own
+// K/V rows have been stored into the paged pool before this kernel runs.
+//
+// Work decomposition.  One workgroup (4 waves) owns a tile of 128 "rows": the G query heads
+// of one kv head times 128/G consecutive chunk rows, so the K/V bytes it reads are shared by
+// all G heads.  Tiles arrive longest-first from the host plan.
+//
+// Transposed formulation.  Per 32 keys the wave computes S^T = K Q^T (M = keys, N = query
+// rows, contraction over d) and O^T += V^T P^T (M = head dim, N = query rows, contraction
+// over keys) with v_mfma_f32_32x32x16_bf16.  Each lane then owns one query row (column
+// n = lane % 32): its 16 accumulator registers of S^T are 16 keys of that row, so the row
+// maximum and sum are register-local except for one exchange with lane ^ 32, and the
+// C-layout of S^T is already the B-operand layout of P^T once the keys of a 16-key step are
+// taken in the order {0-3, 8-11 | 4-7, 12-15}; the V^T operand is staged in LDS in the same
+// order, so P never moves between lanes.
+//
+// K tiles are token-major [16][d] and V tiles are transposed [d][16] in the pool, which is
+// what the A operands want: 8 consecutive d of one key for K, 4+4 consecutive keys of one d
+// for V.  Both are staged through LDS (coalesced 16-byte global loads, padded K rows) and
+// shared by the four waves.
+#include "kernels.h"
+
+namespace heddle {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kBlockTokens = 16;
+constexpr int kChunkTokens = 32;        // keys per main-loop step: two 16-token blocks
+constexpr int kTileRows = 128;          // query rows (heads x chunk rows) per workgroup
+constexpr float kLazyMaxSlack = 8.0f;   // log2 units
+
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+  uint32_t a = __builtin_bit_cast(uint32_t, lo), b = __builtin_bit_cast(uint32_t, hi);
+  a += 0x7fffu + ((a >> 16) & 1u);      // p is finite and non-negative here
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xffff0000u);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+template <int G, int D>
+__global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
+  constexpr int NK = D / 16;             // MFMA steps over d for S^T
+  constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
+  constexpr int R = kTileRows / G;       // chunk rows per workgroup tile
+  constexpr int KPITCH = D + 8;          // padded K row in LDS (elements): rows 16 B apart in banks
+  constexpr int kTileElems = kBlockTokens * D;
+
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[kChunkTokens * KPITCH];
+  __shared__ __attribute__((aligned(16))) uint16_t s_v[2 * kTileElems];
+
+  const int tile = blockIdx.x / a.n_kv_heads;
+  const int h = blockIdx.x - tile * a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int n = lane & 31;               // query row (column of S^T / O^T) within the wave
+  const int hi = lane >> 5;
+
+  const int b = a.tile_b[tile];
+  const int row0 = a.tile_row0[tile];
+  const int rows_n = a.tile_rows_n[tile];
+  const int extent = a.tile_extent[tile];          // keys visible to the tile's last row
+  const int L = a.ctx_len[b];
+  const int kv_len = L + (a.cu_chunk[b + 1] - a.cu_chunk[b]);
+  const int32_t* table = a.block_ids + a.row_off[b];
+
+  // this lane's query row
+  const int n_global = wave * 32 + n;
+  const int g = n_global / R;
+  const int r_in_tile = n_global - g * R;
+  const bool row_valid = r_in_tile < rows_n;
+  const int chunk_row = row0 + min(r_in_tile, rows_n - 1);
+  const int64_t q_row = static_cast<int64_t>(a.cu_chunk[b]) + chunk_row;
+  const int pos = L + chunk_row;                   // last key this row may see
+  const int head = h * G + g;
+
+  // Q^T operand: B[k = d][n = row], 8 consecutive d per lane and step
+  bf16x8 qb[NK];
+  {
+    const uint16_t* qp = a.q + (q_row * a.n_q_heads + head) * D + hi * 8;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) qb[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + kk * 16));
+  }
+
+  f32x16 o[NMT];
+#pragma unroll
+  for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[mt][j] = 0.0f;
+  float m_ref = -INFINITY, l_sum = 0.0f;
+
+  const int64_t head_stride = 2 * kTileElems;
+  const int64_t block_stride = static_cast<int64_t>(a.n_kv_heads) * head_stride;
+  const int n_blocks_needed = (extent + kBlockTokens - 1) / kBlockTokens;
+  const int n_chunks = (extent + kChunkTokens - 1) / kChunkTokens;
+
+  // staging roles: thread -> two 16-byte pieces of K and two of V per chunk
+  //   K piece x: block x, token tid/16, d slice tid%16          -> s_k[(16x + token)*KPITCH + slice*8]
+  //   V piece x: block x, d row tid/2, token half tid%2 (8 keys) -> s_v[x][d][16] with the four
+  //              4-key groups of a row stored in the order {0-3, 8-11, 4-7, 12-15}
+  const int k_tok = tid >> 4, k_slice = tid & 15;
+  const int v_row = tid >> 1, v_half = tid & 1;
+  static_assert(D == 128, "staging roles are written for head_dim 128");
+
+  u32x4 stage_k[2], stage_v[2];
+  auto fetch = [&](int c) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int blk = 2 * c + x;
+      if (blk < n_blocks_needed) {
+        const int phys = table[blk];
+        const uint16_t* t = a.pool + static_cast<int64_t>(phys) * block_stride + h * head_stride;
+        stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_tok * D + k_slice * 8);
+        u32x4 vv = *reinterpret_cast<const u32x4*>(t + kTileElems + v_row * kBlockTokens + v_half * 8);
+        const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist
+        if (nv < 8) {                                              // slots past the cache may hold NaN
+          vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
+          vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
+          vv.z &= (4 < nv ? 0x0000ffffu : 0u) | (5 < nv ? 0xffff0000u : 0u);
+          vv.w &= (6 < nv ? 0x0000ffffu : 0u) | (7 < nv ? 0xffff0000u : 0u);
+        }
+        stage_v[x] = vv;
+      } else {
+        stage_k[x] = u32x4{0u, 0u, 0u, 0u};
+        stage_v[x] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      *reinterpret_cast<u32x4*>(&s_k[(x * kBlockTokens + k_tok) * KPITCH + k_slice * 8]) = stage_k[x];
+      uint16_t* vrow = &s_v[x * kTileElems + v_row * kBlockTokens];
+      *reinterpret_cast<u32x2*>(vrow + v_half * 4) = u32x2{stage_v[x].x, stage_v[x].y};        // keys 8h+0..3
+      *reinterpret_cast<u32x2*>(vrow + 8 + v_half * 4) = u32x2{stage_v[x].z, stage_v[x].w};    // keys 8h+4..7
+    }
+  };
+
+  fetch(0);
+  for (int c = 0; c < n_chunks; ++c) {
+    __syncthreads();                   // every wave is done reading the previous chunk
+    commit();
+    __syncthreads();
+    if (c + 1 < n_chunks) fetch(c + 1);   // next chunk's global loads fly during the math
+
+    const int t0 = c * kChunkTokens;
+
+    // ---- S^T = K Q^T : 32 keys x 32 rows
+    f32x16 s;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s[j] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+      const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&s_k[n * KPITCH + kk * 16 + hi * 8]));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s, 0, 0, 0);
+    }
+
+    // register j of this lane is key t0 + 8*(j/4) + 4*hi + j%4 of its row
+    float z[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) z[j] = s[j] * a.scale_log2;
+    if (t0 + kChunkTokens - 1 > L + row0) {          // chunk reaches the causal edge of some row
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int t = t0 + 8 * (j >> 2) + 4 * hi + (j & 3);
+        if (t > pos) z[j] = -INFINITY;
+      }
+    }
+
+    float mx = z[0];
+#pragma unroll
+    for (int j = 1; j < 16; ++j) mx = fmaxf(mx, z[j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazyMaxSlack) != 0) {
+      const float m_new = fmaxf(m_ref, mx);
+      const float shrink = __builtin_amdgcn_exp2f(m_ref - m_new);
+      l_sum *= shrink;
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[mt][j] *= shrink;
+      m_ref = m_new;
+    }
+
+    float p[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      p[j] = __builtin_amdgcn_exp2f(z[j] - m_ref);
+      l_sum += p[j];
+    }
+
+    // ---- O^T += V^T P^T : two 16-key steps, NMT tiles of 32 head-dim rows
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      u32x4 pw;
+      pw.x = pack_bf16_rne(p[8 * st + 0], p[8 * st + 1]);
+      pw.y = pack_bf16_rne(p[8 * st + 2], p[8 * st + 3]);
+      pw.z = pack_bf16_rne(p[8 * st + 4], p[8 * st + 5]);
+      pw.w = pack_bf16_rne(p[8 * st + 6], p[8 * st + 7]);
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt) {
+        const bf16x8 va = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st * kTileElems + (mt * 32 + n) * kBlockTokens + hi * 8]));
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[mt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- normalise and store: register j of tile mt is head-dim element mt*32 + 8*(j/4) + 4*hi + j%4
+  l_sum += __shfl_xor(l_sum, 32, 64);
+  if (row_valid) {
+    const float inv = 1.0f / l_sum;
+    uint16_t* op = a.out + (q_row * a.n_q_heads + head) * D;
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        u32x2 w;
+        w.x = static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 0] * inv)) |
+              (static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 1] * inv)) << 16);
+        w.y = static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 2] * inv)) |
+              (static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 3] * inv)) << 16);
+        *reinterpret_cast<u32x2*>(op + mt * 32 + 8 * jq + 4 * hi) = w;
+      }
+    if (a.lse != nullptr && hi == 0)
+      a.lse[q_row * a.n_q_heads + head] = (m_ref + __builtin_log2f(l_sum)) * 0.6931471805599453f;
+  }
+}
+
+template <int G, int D>
+hipError_t launch_append_t(const AppendLaunch& a, hipStream_t stream) {
+  const dim3 grid(static_cast<unsigned>(a.n_tiles) * static_cast<unsigned>(a.n_kv_heads));
+  hipLaunchKernelGGL((append_attn_kernel<G, D>), grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool append_shape_supported(int32_t group, int32_t head_dim) {
+  return head_dim == 128 && (group == 1 || group == 2 || group == 4 || group == 8);
+}
+
+int32_t append_tile_rows(int32_t group) { return kTileRows / group; }
+
+hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream) {
+  const int G = a.n_q_heads / a.n_kv_heads;
+  if (a.head_dim != 128) return hipErrorInvalidValue;
+  switch (G) {
+    case 1: return launch_append_t<1, 128>(a, stream);
+    case 2: return launch_append_t<2, 128>(a, stream);
+    case 4: return launch_append_t<4, 128>(a, stream);
+    case 8: return launch_append_t<8, 128>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace heddle

@@ -48,6 +48,27 @@ struct KvWriteLaunch {
 };
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream);
 
+// Arguments of the causal chunked-append attention pass.  All pointers are device memory.
+struct AppendLaunch {
+  const uint16_t* pool;
+  const int32_t* row_off;
+  const int32_t* block_ids;
+  const int32_t* ctx_len;      // [B]   tokens retained before the chunk
+  const int32_t* cu_chunk;     // [B+1] prefix sums of chunk lengths
+  const int32_t* tile_b;       // [n_tiles] plan arrays, longest tile first
+  const int32_t* tile_row0;
+  const int32_t* tile_rows_n;
+  const int32_t* tile_extent;
+  const uint16_t* q;           // bf16 [sum C][n_q][d]
+  uint16_t* out;               // bf16 [sum C][n_q][d]
+  float* lse;                  // f32 [sum C][n_q] or nullptr
+  int32_t n_tiles, n_q_heads, n_kv_heads, head_dim;
+  float scale_log2;
+};
+bool append_shape_supported(int32_t group, int32_t head_dim);
+int32_t append_tile_rows(int32_t group);   // chunk rows per workgroup tile
+hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
 
 }  // namespace heddle

@@ -1,0 +1,180 @@
+"""Parity of heddle_attn_append with the float64 oracle, through the C ABI (needs the GPU)."""
+import math
+
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+from oracle import attention as oa
+from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64,
+                            bf16_to_host_bits)
+
+pytestmark = pytest.mark.gpu
+
+
+def small(seed, L, C, n_q=8, n_kv=2, d=128, **kw):
+    return hw.build_case(entropy=[0, seed], lens=L, chunk_lens=C, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=d,
+                         threads=4, **kw)
+
+
+def oracle_append(c, rows=None):
+    pool = c["pool"].copy()
+    out, lse, spread = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"], c["k_new"],
+                                 c["v_new"], c["n_kv_heads"], rows=rows, with_spread=True)
+    return pool, out, lse, spread
+
+
+RAGGED_L = [0, 1, 15, 16, 17, 100, 0, 500, 33, 1000]
+RAGGED_C = [1, 40, 1, 16, 33, 31, 130, 7, 64, 129]
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8)])
+def test_ragged_append_all_head_shapes(n_q, n_kv):
+    c = small(40, RAGGED_L, RAGGED_C, n_q=n_q, n_kv=n_kv)
+    print("append ragged", n_q, n_kv, flush=True)
+    dc = DeviceCase(c)
+    out, lse = dc.append()
+    pool, ref, ref_lse, spread = oracle_append(c)
+    assert np.array_equal(dc.pool_bits(), pool), "pool after append differs from the oracle's"
+    assert_close(out, ref, "append out", spread)
+    assert_lse_close(lse, ref_lse, "append lse")
+
+
+def test_append_equals_token_by_token_decode_on_gpu():
+    L, C = [0, 5, 16, 300], [3, 20, 1, 37]
+    c = small(41, L, C)
+    dc = DeviceCase(c)
+    out, lse = dc.append()
+    # the pool now holds the chunk: decode each chunk row's query at len = L + i + 1
+    for b in range(4):
+        for i in sorted(x for x in {0, 1, C[b] // 2, C[b] - 1} if 0 <= x < C[b]):
+            r = int(c["cu_chunk"][b]) + i
+            lens = np.maximum(np.array(L), 1)
+            lens[b] = L[b] + i + 1
+            qb = np.zeros((4,) + c["q"].shape[1:], dtype=np.uint16)
+            qb[b] = c["q"][r]
+            dc2_q = to_dev_bf16(qb)
+            import torch
+            o = torch.empty((4,) + c["q"].shape[1:], dtype=torch.bfloat16, device="cuda")
+            ls = torch.empty((4, c["n_q_heads"]), dtype=torch.float32, device="cuda")
+            dc.ctx.attn_decode(lens, c["row_off"], dc.row_off, dc.block_ids, dc2_q, o, ls)
+            torch.cuda.synchronize()
+            got = bits_to_f64(bf16_to_host_bits(o))[b]
+            # both are bf16-rounded results of the same sum: allow two output ulps plus weight rounding
+            assert np.allclose(got, out[r], rtol=2.0 ** -6, atol=2e-3), (b, i)
+            assert np.abs(ls.cpu().numpy()[b] - lse[r]).max() < 1e-3, (b, i)
+
+
+def test_append_in_two_pieces_equals_one_piece_on_gpu():
+    L, C = [7, 400], [50, 90]
+    c = small(42, L, C)
+    one = DeviceCase(c)
+    out1, lse1 = one.append()
+    C1 = [20, 33]
+    cu = c["cu_chunk"]
+    rows1 = np.concatenate([np.arange(cu[b], cu[b] + C1[b]) for b in range(2)])
+    rows2 = np.concatenate([np.arange(cu[b] + C1[b], cu[b + 1]) for b in range(2)])
+    cA = dict(c, q=c["q"][rows1], k_new=c["k_new"][rows1], v_new=c["v_new"][rows1],
+              cu_chunk=np.array([0, C1[0], C1[0] + C1[1]], dtype=np.int32))
+    two = DeviceCase(cA)
+    outA, lseA = two.append()
+    cB = dict(c, q=c["q"][rows2], k_new=c["k_new"][rows2], v_new=c["v_new"][rows2],
+              lens=np.array([L[0] + C1[0], L[1] + C1[1]], dtype=np.int32),
+              cu_chunk=np.array([0, C[0] - C1[0], C[0] - C1[0] + C[1] - C1[1]], dtype=np.int32))
+    import torch
+    two.case = cB
+    two.q = to_dev_bf16(cB["q"])
+    two.out = torch.empty(cB["q"].shape, dtype=torch.bfloat16, device="cuda")
+    two.lse = torch.empty(cB["q"].shape[:2], dtype=torch.float32, device="cuda")
+    outB, lseB = two.append()
+    assert np.array_equal(one.pool_bits(), two.pool_bits())
+    assert np.allclose(out1[rows1], outA, rtol=2.0 ** -6, atol=2e-3)
+    assert np.allclose(out1[rows2], outB, rtol=2.0 ** -6, atol=2e-3)
+    assert np.abs(lse1[rows2] - lseB).max() < 1e-3
+
+
+def test_append_needles():
+    """Dominant keys with 1000-markers in V: every chunk row's own position (the causal edge),
+    the last retained position, the first, and a block boundary inside the chunk."""
+    n_q, n_kv, d = 8, 2, 128
+    G = n_q // n_kv
+    L, C = [50], [40]
+    base = small(43, L, C, poison=True)
+    for h in range(n_kv):
+        base["q"][:, h * G:(h + 1) * G] = base["q"][:, h * G:h * G + 1]
+
+    def key_for(qrow):
+        qv = bits_to_f64(qrow)
+        return hw.f32_to_bf16_bits((40.0 * math.sqrt(d) * qv / (qv @ qv)).astype(np.float32))
+
+    # (a) every row finds its own key: logit 40 on the diagonal, later rows' keys are masked
+    c = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in base.items()}
+    for i in range(C[0]):
+        for h in range(n_kv):
+            c["k_new"][i, h] = key_for(c["q"][i, h * G])
+            c["v_new"][i, h] = hw.f32_to_bf16_bits(np.full(d, 100.0 + i, dtype=np.float32))
+    out, lse = DeviceCase(c).append()
+    pool, ref, ref_lse, spread = oracle_append(c)
+    assert_close(out, ref, "needle diagonal", spread)
+    assert_lse_close(lse, ref_lse)
+    # keys of earlier rows are random w.r.t. this row's q: its own key dominates
+    for i in range(C[0]):
+        assert np.abs(out[i] - (100.0 + i)).max() < 1.0, i
+
+    # (b) needle in the retained context at position pos, seen by every row
+    for pos in (0, 15, 16, L[0] - 1):
+        c = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in base.items()}
+        c["q"][:] = c["q"][0]                         # one query direction for all rows
+        blk = c["block_ids"][pos // 16]
+        for h in range(n_kv):
+            hw.k_view(c["pool"])[blk, h, pos % 16] = key_for(c["q"][0, h * G])
+            marker = np.zeros(d, dtype=np.float32)
+            marker[(pos + h) % d] = 1000.0
+            hw.v_view(c["pool"])[blk, h, :, pos % 16] = hw.f32_to_bf16_bits(marker)
+        out, lse = DeviceCase(c).append()
+        pool, ref, ref_lse, spread = oracle_append(c)
+        assert_close(out, ref, f"needle at {pos}", spread)
+        assert_lse_close(lse, ref_lse)
+        for j in range(n_q):
+            assert np.abs(out[:, j, (pos + j // G) % d] - 1000.0).max() < 8.0, (pos, j)
+
+
+def test_append_rejects_bad_arguments():
+    import paper_2603_28101_amd as heddle
+    c = small(44, [10, 20], [5, 6])
+    dc = DeviceCase(c)
+    before = dc.pool_bits().copy()
+    good = dict(c)
+    for bad in (dict(lens=np.array([-1, 20], dtype=np.int32)),
+                dict(cu_chunk=np.array([0, 5, 5], dtype=np.int32)),
+                dict(lens=np.array([10, 40], dtype=np.int32))):        # table too short for L + C
+        dc.case = dict(good, **bad)
+        with pytest.raises(heddle.HeddleError) as e:
+            dc.append()
+        assert e.value.code == heddle.E_INVAL
+    assert np.array_equal(dc.pool_bits(), before)
+    dc.case = good
+    out, _ = dc.append()
+    assert_close(out, oracle_append(c)[1])
+
+
+def test_full_size_append_workload_sampled():
+    c = hw.make_workload(5, 0, threads=16)
+    w = c["workload"]
+    print(f"append workload: pool {c['pool'].nbytes / 1e9:.2f} GB, context {int(c['lens'].sum())}, "
+          f"chunk rows {int(c['chunk_lens'].sum())}", flush=True)
+    dc = DeviceCase(c)
+    out, lse = dc.append()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    cu = c["cu_chunk"]
+    rng = np.random.default_rng(5)
+    rows = []
+    for b in [int(np.argmax(c["lens"])), int(np.argmin(c["lens"])), int(rng.integers(0, 32))]:
+        C = int(cu[b + 1] - cu[b])
+        rows += [int(cu[b]) + r for r in sorted({0, 1, C // 2, C - 2, C - 1, 31, 32})if 0 <= r < C]
+    rows = sorted(set(rows))
+    pool, ref, ref_lse, spread = oracle_append(c, rows=rows)
+    assert_close(out[rows], ref[rows], "append workload", spread[rows])
+    assert_lse_close(lse[rows], ref_lse[rows], "append workload lse")
+    # the whole chunk is in the pool, bit for bit, and nothing else changed
+    assert np.array_equal(dc.pool_bits(), pool)
