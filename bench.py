@@ -140,6 +140,16 @@ def main():
     torch.cuda.synchronize()
     stream_gbps = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    # plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE
+    # counters of a profiling run are scaled by
+    cal_src = pool.view(torch.int16).reshape(-1)[: 64 * 1024 * 1024]
+    cal_dst = torch.empty_like(cal_src)
+    with torch.cuda.stream(stream):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+
+    roofline["traffic"] = recorded_traffic(w, roofline["kernel"])
+
     result = {
         "metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -157,6 +167,30 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(case, w, np)
     print(json.dumps(result))
+
+
+KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_attn_kernel": "append_kernels.hip"}
+
+
+def recorded_traffic(w, kernel):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 counters and
+    written into the kernel's summary under profiles/ (lines `traffic_bytes_per_launch = N` and
+    `kernel_source_sha256 = H`); None if there is no record or the kernel source has changed
+    since the counters were taken."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"{kernel}__{w.name}.md")
+    src = os.path.join(ROOT, "paper_2603_28101_amd", "csrc", KERNEL_SOURCES[kernel])
+    try:
+        text = open(path).read()
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", text)
+    h = re.search(r"kernel_source_sha256\s*=\s*([0-9a-f]{64})", text)
+    if not m or not h or h.group(1) != digest:
+        return None
+    return int(m.group(1))
 
 
 def cpu_baseline(case, w, np):

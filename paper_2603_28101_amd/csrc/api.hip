@@ -16,7 +16,7 @@ using namespace heddle;
 namespace {
 
 constexpr int kStagingSlots = 8;
-constexpr int kTimedKernels = 4;       // decode, combine, append, kv write
+constexpr int kTimedKernels = 4;       // split-K decode, combine, append, kv write
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
 
 struct StagingSlot {
@@ -408,7 +408,7 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     TimedScope t(ctx, 0, stream);
     HEDDLE_HIP(launch_decode_splitk(dl, stream));
   }
-  {
+  if (n_parts > static_cast<size_t>(B)) {     // some trajectory was split
     TimedScope t(ctx, 1, stream);
     HEDDLE_HIP(launch_decode_combine(dl, stream));
   }

@@ -1,4 +1,5 @@
-// Split-K decode attention over a paged KV pool, and the log-sum-exp merge of its parts.
+// Split-K decode attention over a paged KV pool, and the log-sum-exp merge of the parts of
+// trajectories that were split (an unsplit trajectory is finished by its only item).
 //
 // One query token per trajectory attends to its whole retained context (paper Sec. 2.1:
 // generation steps of a multi-step trajectory; Sec. 4.2: the KV cache persists between
@@ -432,13 +433,13 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerGroup * 64) {
-    const int g = idx / D;
-    const int e = idx - g * D;
-    float M = s_f[0][0][g];
+
+  // Merged (reference max, sums, accumulator) of the four waves for output element (g, e).
+  auto wave_merge = [&](int g, int e, float& M, float& val, float& Lr, float& Le) {
+    M = s_f[0][0][g];
 #pragma unroll
     for (int w = 1; w < kWavesPerGroup; ++w) M = fmaxf(M, s_f[w][0][g]);
-    float val = 0.0f, Lr = 0.0f, Le = 0.0f;
+    val = 0.0f, Lr = 0.0f, Le = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWavesPerGroup; ++w) {
       const float f = __builtin_amdgcn_exp2f(s_f[w][0][g] - M);   // 0 for a wave that had no block
@@ -446,6 +447,25 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
       Lr = fmaf(f, s_f[w][1][g], Lr);
       Le = fmaf(f, s_f[w][2][g], Le);
     }
+  };
+  const int ns = a.nsplit[b];
+  const int64_t oj0 = static_cast<int64_t>(b) * a.n_q_heads + h * G;
+
+  if (ns == 1) {                            // the item is the whole trajectory: finish it here
+    for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerGroup * 64) {
+      const int g = idx / D, e = idx - g * D;
+      float M, val, Lr, Le;
+      wave_merge(g, e, M, val, Lr, Le);
+      a.out[(oj0 + g) * D + e] = f32_to_bf16_rne(val / Lr);
+      if (a.lse != nullptr && e == 0) a.lse[oj0 + g] = (M + __builtin_log2f(Le)) * 0.6931471805599453f;
+    }
+    return;
+  }
+
+  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerGroup * 64) {
+    const int g = idx / D, e = idx - g * D;
+    float M, val, Lr, Le;
+    wave_merge(g, e, M, val, Lr, Le);
     const int64_t pj = static_cast<int64_t>(slot) * a.n_q_heads + h * G + g;
     a.part_acc[pj * D + e] = val;
     if (e == 0) {
@@ -456,14 +476,18 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
   }
 }
 
-// One workgroup per (trajectory, query head): merges the trajectory's parts.
+// Merges the parts of every trajectory that was split; one workgroup per (trajectory, query
+// head).  (Merging inside the split-K kernel by the last item to arrive was tried: the
+// device-scope fences it needs write back and invalidate the per-XCD L2 and doubled the
+// kernel's duration.)
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeLaunch a) {
   const int b = blockIdx.x / a.n_q_heads;
+  const int ns = a.nsplit[b];
+  if (ns == 1) return;                      // finished by its only item
   const int j = blockIdx.x - b * a.n_q_heads;
   const int e = threadIdx.x;
   const int p0 = a.part_off[b];
-  const int ns = a.nsplit[b];
   float M = -INFINITY;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 4]);
   float num = 0.0f, den = 0.0f, den_exact = 0.0f;
