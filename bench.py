@@ -93,7 +93,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.timing_enable(True)            # HIP events around each kernel, on the launch stream
+    # HIP events around every 4th launch of each kernel, on the launch stream (an event pair
+    # costs a few microseconds of stream time, so not every step carries one)
+    ctx.timing_enable(4)
     # a full Python garbage collection (tens of ms with torch loaded) must not land in the
     # timed region: collect now, keep the collector off while timing
     gc.collect()
@@ -107,7 +109,7 @@ def main():
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     aux_us = ctx.timing_read(1)[0] if w.kind == "decode" else ctx.timing_read(3)[0]
-    ctx.timing_enable(False)
+    ctx.timing_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     if w.kind == "decode":

@@ -184,7 +184,9 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
  * Average duration in microseconds of the dominant kernel of the last
  * `heddle_attn_decode` / `heddle_attn_append` calls, measured with HIP events
  * recorded on the caller's stream around that kernel.  Recording is off by
- * default; heddle_timing_enable(ctx, 1) clears the statistics and turns it on.
+ * default; heddle_timing_enable(ctx, N) with N >= 1 clears the statistics and
+ * records every N-th launch of each kernel (each recorded launch costs two
+ * event records, a few microseconds of stream time); 0 turns it off.
  * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
  * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write. */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);

@@ -223,8 +223,9 @@ class Context:
         _check(lib.heddle_attn_append(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_append")
 
     # ---- measurement
-    def timing_enable(self, on: bool = True) -> None:
-        _check(lib.heddle_timing_enable(self._h, 1 if on else 0), "heddle_timing_enable")
+    def timing_enable(self, every: int = 1) -> None:
+        """every = N >= 1: record every N-th launch of each kernel; 0 / False: off."""
+        _check(lib.heddle_timing_enable(self._h, int(every)), "heddle_timing_enable")
 
     def timing_read(self, which: int):
         us, n = C.c_double(), C.c_int64()

@@ -29,6 +29,7 @@ struct StagingSlot {
 struct KernelTimer {
   std::vector<hipEvent_t> start, stop;
   int64_t recorded = 0;                // launches recorded since enable
+  int64_t seen = 0;                    // launches since enable
 };
 
 }  // namespace
@@ -50,7 +51,7 @@ struct heddle_ctx {
   float* dev_part_ml = nullptr;
   size_t dev_part_ml_elems = 0;
 
-  bool timing_on = false;
+  int32_t timing_every = 0;             // 0 = off; N = record every N-th launch of each kernel
   KernelTimer timers[kTimedKernels];
 
   // host scratch reused between calls
@@ -143,10 +144,12 @@ struct TimedScope {
   hipStream_t stream;
   int idx = -1;
   TimedScope(heddle_ctx* c, int w, hipStream_t s) : ctx(c), which(w), stream(s) {
-    if (ctx->timing_on) {
+    if (ctx->timing_every > 0) {
       KernelTimer& t = ctx->timers[which];
-      idx = static_cast<int>(t.recorded % kEventPairs);
-      (void)hipEventRecord(t.start[idx], stream);
+      if (t.seen++ % ctx->timing_every == 0) {
+        idx = static_cast<int>(t.recorded % kEventPairs);
+        (void)hipEventRecord(t.start[idx], stream);
+      }
     }
   }
   ~TimedScope() {
@@ -331,39 +334,39 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
                    sizeof(float));
   if (rc != HEDDLE_OK) return rc;
 
-  // plan image: lens[B] | first_pos[B] | cu_rows[B+1] | part_off[B+1] | nsplit[B] | 4 x items
-  const size_t words = 5 * static_cast<size_t>(B) + 2 + 4 * n_items;
+  // plan image: item records | trajectory records | first_pos[B] | cu_rows[B+1]
+  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 2 * static_cast<size_t>(B) + 1;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
   int32_t* w = slot->host;
-  int32_t* h_lens = w;
-  int32_t* h_first = h_lens + B;
+  DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
+  DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * n_items);
+  int32_t* h_first = w + 8 * n_items + 2 * static_cast<size_t>(B);
   int32_t* h_cu = h_first + B;
-  int32_t* h_part_off = h_cu + B + 1;
-  int32_t* h_nsplit = h_part_off + B + 1;
-  int32_t* h_item_b = h_nsplit + B;
-  int32_t* h_item_s = h_item_b + n_items;
-  int32_t* h_item_lo = h_item_s + n_items;
-  int32_t* h_item_hi = h_item_lo + n_items;
+  for (size_t i = 0; i < n_items; ++i) {
+    const DecodeItem& it = ctx->items[i];
+    DecodeItemRec& r = h_items[i];
+    r.b = it.b;
+    r.slot = ctx->part_off[it.b] + it.s;
+    r.blk_begin = it.blk_begin;
+    r.blk_end = it.blk_end;
+    r.len = args->len_host[it.b];
+    r.table_off = args->row_off_host[it.b];
+    r.nsplit = ctx->nsplit[it.b];
+    r.pad = 0;
+  }
   for (int32_t b = 0; b < B; ++b) {
-    h_lens[b] = args->len_host[b];
+    h_trajs[b].part_off = ctx->part_off[b];
+    h_trajs[b].nsplit = ctx->nsplit[b];
     h_first[b] = args->len_host[b] - 1;
     h_cu[b] = b;
-    h_nsplit[b] = ctx->nsplit[b];
   }
   h_cu[B] = B;
-  std::memcpy(h_part_off, ctx->part_off.data(), sizeof(int32_t) * (static_cast<size_t>(B) + 1));
-  for (size_t i = 0; i < n_items; ++i) {
-    h_item_b[i] = ctx->items[i].b;
-    h_item_s[i] = ctx->items[i].s;
-    h_item_lo[i] = ctx->items[i].blk_begin;
-    h_item_hi[i] = ctx->items[i].blk_end;
-  }
   rc = upload(ctx, slot, words, stream);
   if (rc != HEDDLE_OK) return rc;
-  ctx->enqueued = true;
   const int32_t* d = ctx->dev_plan;
+  ctx->enqueued = true;
 
   if (args->k_new != nullptr) {
     KvWriteLaunch kw{};
@@ -384,15 +387,9 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
 
   DecodeLaunch dl{};
   dl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
-  dl.row_off = args->row_off;
   dl.block_ids = args->block_ids;
-  dl.lens = d + (h_lens - w);
-  dl.item_b = d + (h_item_b - w);
-  dl.item_s = d + (h_item_s - w);
-  dl.item_blk_begin = d + (h_item_lo - w);
-  dl.item_blk_end = d + (h_item_hi - w);
-  dl.part_off = d + (h_part_off - w);
-  dl.nsplit = d + (h_nsplit - w);
+  dl.items = reinterpret_cast<const DecodeItemRec*>(d);
+  dl.trajs = reinterpret_cast<const DecodeTrajRec*>(d + 8 * n_items);
   dl.q = static_cast<const uint16_t*>(args->q);
   dl.part_acc = ctx->dev_part_acc;
   dl.part_ml = ctx->dev_part_ml;
@@ -524,9 +521,10 @@ int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {
         t.stop.push_back(b);
       }
       t.recorded = 0;
+      t.seen = 0;
     }
   }
-  ctx->timing_on = on != 0;
+  ctx->timing_every = on > 0 ? on : 0;
   return HEDDLE_OK;
 }
 

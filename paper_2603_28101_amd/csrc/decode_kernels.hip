@@ -233,12 +233,13 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
   const int my_tok = (n0 / G) * TPI + r;    // token within the block
   const int my_g0 = n0 % G;                 // first (or only) head; the second is my_g0 + 1
 
-  const int b = a.item_b[item];
-  const int blk_begin = a.item_blk_begin[item];
-  const int blk_end = a.item_blk_end[item];
-  const int len = a.lens[b];
-  const int32_t* table = a.block_ids + a.row_off[b];
-  const int slot = a.part_off[b] + a.item_s[item];
+  const DecodeItemRec rec = a.items[item];
+  const int b = rec.b;
+  const int blk_begin = rec.blk_begin;
+  const int blk_end = rec.blk_end;
+  const int len = rec.len;
+  const int32_t* table = a.block_ids + rec.table_off;
+  const int slot = rec.slot;
 
   // each wave streams a contiguous quarter of the item's blocks: [w_begin, w_begin + nw)
   const int n_item_blk = blk_end - blk_begin;
@@ -448,7 +449,7 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
       Le = fmaf(f, s_f[w][2][g], Le);
     }
   };
-  const int ns = a.nsplit[b];
+  const int ns = rec.nsplit;
   const int64_t oj0 = static_cast<int64_t>(b) * a.n_q_heads + h * G;
 
   if (ns == 1) {                            // the item is the whole trajectory: finish it here
@@ -483,11 +484,12 @@ __global__ __launch_bounds__(kWavesPerGroup * 64, 2) void decode_splitk_kernel(D
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeLaunch a) {
   const int b = blockIdx.x / a.n_q_heads;
-  const int ns = a.nsplit[b];
+  const DecodeTrajRec tr = a.trajs[b];
+  const int ns = tr.nsplit;
   if (ns == 1) return;                      // finished by its only item
   const int j = blockIdx.x - b * a.n_q_heads;
   const int e = threadIdx.x;
-  const int p0 = a.part_off[b];
+  const int p0 = tr.part_off;
   float M = -INFINITY;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 4]);
   float num = 0.0f, den = 0.0f, den_exact = 0.0f;

@@ -6,18 +6,30 @@
 
 namespace heddle {
 
-// Arguments of the split-K decode pass.  All pointers are device memory.
+// One split-K work item as the decode kernel reads it: a single 32-byte record, so that a
+// workgroup learns everything about its item with one scalar load.
+struct DecodeItemRec {
+  int32_t b;            // trajectory
+  int32_t slot;         // partial slot = part_off[b] + split index
+  int32_t blk_begin;    // logical blocks [blk_begin, blk_end) of the trajectory
+  int32_t blk_end;
+  int32_t len;          // context length of the trajectory
+  int32_t table_off;    // row_off[b]: start of its row in block_ids
+  int32_t nsplit;       // items of the trajectory
+  int32_t pad;
+};
+
+struct DecodeTrajRec {
+  int32_t part_off;     // first partial slot of the trajectory
+  int32_t nsplit;
+};
+
+// Arguments of the split-K decode pass.  Pointers are device-accessible memory.
 struct DecodeLaunch {
   const uint16_t* pool;        // bf16 [n_blocks][n_kv]{K tile [16][d], V tile [d][16]}
-  const int32_t* row_off;      // [B+1]
   const int32_t* block_ids;    // CSR block table
-  const int32_t* lens;         // [B]
-  const int32_t* item_b;       // [n_items] plan arrays
-  const int32_t* item_s;
-  const int32_t* item_blk_begin;
-  const int32_t* item_blk_end;
-  const int32_t* part_off;     // [B+1]
-  const int32_t* nsplit;       // [B]
+  const DecodeItemRec* items;  // [n_items] longest first
+  const DecodeTrajRec* trajs;  // [B]
   const uint16_t* q;           // bf16 [B][n_q][d]
   float* part_acc;             // f32 [n_parts][n_q][d]   unnormalised sum of p * v
   float* part_ml;              // f32 [n_parts][n_q][4]   (max logit in log2 units, sum of bf16-rounded p,
