@@ -10,7 +10,8 @@
 // of one kv head times 128/G consecutive chunk rows, so the K/V bytes it reads are shared by
 // all G heads.  Tiles arrive longest-first from the host plan.
 //
-// Transposed formulation.  Per 32 keys the wave computes S^T = K Q^T (M = keys, N = query
+// Transposed formulation.  Per 32 keys (two such tiles per 64-key main-loop step) the wave
+// computes S^T = K Q^T (M = keys, N = query
 // rows, contraction over d) and O^T += V^T P^T (M = head dim, N = query rows, contraction
 // over keys) with v_mfma_f32_32x32x16_bf16.  Each lane then owns one query row (column
 // n = lane % 32): its 16 accumulator registers of S^T are 16 keys of that row, so the row
@@ -21,8 +22,9 @@
 //
 // K tiles are token-major [16][d] and V tiles are transposed [d][16] in the pool, which is
 // what the A operands want: 8 consecutive d of one key for K, 4+4 consecutive keys of one d
-// for V.  Both are staged through LDS (coalesced 16-byte global loads, padded K rows) and
-// shared by the four waves.
+// for V.  Both are staged through LDS (coalesced 16-byte global loads into registers one step
+// ahead, XOR-swizzled K rows, double buffer, one barrier per 64 keys) and shared by the four
+// waves.
 #include "kernels.h"
 
 namespace heddle {
@@ -35,34 +37,36 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kBlockTokens = 16;
-constexpr int kChunkTokens = 32;        // keys per main-loop step: two 16-token blocks
+constexpr int kChunkBlocks = 4;
+constexpr int kChunkTokens = kChunkBlocks * kBlockTokens;   // keys per main-loop step
 constexpr int kTileRows = 128;          // query rows (heads x chunk rows) per workgroup
 constexpr float kLazyMaxSlack = 8.0f;   // log2 units
 
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
-  uint32_t a = __builtin_bit_cast(uint32_t, lo), b = __builtin_bit_cast(uint32_t, hi);
-  a += 0x7fffu + ((a >> 16) & 1u);      // p is finite and non-negative here
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
-}
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
+// two floats -> packed bf16 pair (round to nearest even), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <int G, int D>
 __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
+  static_assert(D == 128, "staging roles and swizzle are written for head_dim 128");
   constexpr int NK = D / 16;             // MFMA steps over d for S^T
   constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
   constexpr int R = kTileRows / G;       // chunk rows per workgroup tile
-  constexpr int KPITCH = D + 8;          // padded K row in LDS (elements): rows 16 B apart in banks
   constexpr int kTileElems = kBlockTokens * D;
+  constexpr int kStageK = kChunkTokens * D;            // elements of K per LDS stage
+  constexpr int kStageV = kChunkBlocks * kTileElems;   // elements of V per LDS stage
 
-  __shared__ __attribute__((aligned(16))) uint16_t s_k[kChunkTokens * KPITCH];
-  __shared__ __attribute__((aligned(16))) uint16_t s_v[2 * kTileElems];
+  // Two stages (double buffer).  K rows are 256 B = 16 slots of 16 B; slot c of key row t is
+  // stored at slot c ^ (t & 15), so that the 32 lanes reading the same d-slice of 32
+  // different keys spread over all banks.  V rows are 32 B with their four 4-key groups in
+  // the order {0-3, 8-11, 4-7, 12-15}.
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[2][kStageK];
+  __shared__ __attribute__((aligned(16))) uint16_t s_v[2][kStageV];
 
   const int tile = blockIdx.x / a.n_kv_heads;
   const int h = blockIdx.x - tile * a.n_kv_heads;
@@ -110,21 +114,30 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
   const int n_blocks_needed = (extent + kBlockTokens - 1) / kBlockTokens;
   const int n_chunks = (extent + kChunkTokens - 1) / kChunkTokens;
 
-  // staging roles: thread -> two 16-byte pieces of K and two of V per chunk
-  //   K piece x: block x, token tid/16, d slice tid%16          -> s_k[(16x + token)*KPITCH + slice*8]
-  //   V piece x: block x, d row tid/2, token half tid%2 (8 keys) -> s_v[x][d][16] with the four
-  //              4-key groups of a row stored in the order {0-3, 8-11, 4-7, 12-15}
+  // staging roles: per chunk and thread one 16-byte piece of K and one of V from each block
+  //   K piece x: key row 16x + tid/16, d slice tid%16
+  //   V piece x: block x, d row tid/2, key half tid%2 (8 keys)
   const int k_tok = tid >> 4, k_slice = tid & 15;
   const int v_row = tid >> 1, v_half = tid & 1;
-  static_assert(D == 128, "staging roles are written for head_dim 128");
 
-  u32x4 stage_k[2], stage_v[2];
-  auto fetch = [&](int c) {
+  // Physical block ids are read through the constant address space (scalar loads, the table
+  // does not change during the launch) one chunk ahead of the K/V loads that need them, so
+  // that no K/V load waits for a table lookup.
+  typedef const __attribute__((address_space(4))) int32_t* const_ids_t;
+  const const_ids_t ctable = (const_ids_t)(reinterpret_cast<uintptr_t>(table));
+  int ids[kChunkBlocks];
+  auto load_ids = [&](int c) {
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int blk = 2 * c + x;
+    for (int x = 0; x < kChunkBlocks; ++x) ids[x] = ctable[min(kChunkBlocks * c + x, n_blocks_needed - 1)];
+  };
+
+  u32x4 stage_k[kChunkBlocks], stage_v[kChunkBlocks];
+  auto fetch = [&](int c) {               // uses the ids loaded by the preceding load_ids(c)
+#pragma unroll
+    for (int x = 0; x < kChunkBlocks; ++x) {
+      const int blk = kChunkBlocks * c + x;
       if (blk < n_blocks_needed) {
-        const int phys = table[blk];
+        const int phys = ids[x];
         const uint16_t* t = a.pool + static_cast<int64_t>(phys) * block_stride + h * head_stride;
         stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_tok * D + k_slice * 8);
         u32x4 vv = *reinterpret_cast<const u32x4*>(t + kTileElems + v_row * kBlockTokens + v_half * 8);
@@ -142,51 +155,64 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
       }
     }
   };
-  auto commit = [&]() {
+  auto commit = [&](int st) {
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      *reinterpret_cast<u32x4*>(&s_k[(x * kBlockTokens + k_tok) * KPITCH + k_slice * 8]) = stage_k[x];
-      uint16_t* vrow = &s_v[x * kTileElems + v_row * kBlockTokens];
+    for (int x = 0; x < kChunkBlocks; ++x) {
+      const int row = x * kBlockTokens + k_tok;
+      *reinterpret_cast<u32x4*>(&s_k[st][row * D + ((k_slice ^ k_tok) * 8)]) = stage_k[x];
+      uint16_t* vrow = &s_v[st][x * kTileElems + v_row * kBlockTokens];
       *reinterpret_cast<u32x2*>(vrow + v_half * 4) = u32x2{stage_v[x].x, stage_v[x].y};        // keys 8h+0..3
       *reinterpret_cast<u32x2*>(vrow + 8 + v_half * 4) = u32x2{stage_v[x].z, stage_v[x].w};    // keys 8h+4..7
     }
   };
 
+  load_ids(0);
   fetch(0);
+  load_ids(1);
+  commit(0);
+  if (n_chunks > 1) fetch(1);
+  load_ids(2);
   for (int c = 0; c < n_chunks; ++c) {
-    __syncthreads();                   // every wave is done reading the previous chunk
-    commit();
-    __syncthreads();
-    if (c + 1 < n_chunks) fetch(c + 1);   // next chunk's global loads fly during the math
+    const int st = c & 1;
+    __syncthreads();                       // stage st is complete; nobody reads stage st^1 any more
+    if (c + 1 < n_chunks) commit(st ^ 1);
+    if (c + 2 < n_chunks) fetch(c + 2);    // global loads fly during the math below
+    load_ids(c + 3);                       // clamped to the tile's last block
 
     const int t0 = c * kChunkTokens;
 
-    // ---- S^T = K Q^T : 32 keys x 32 rows
-    f32x16 s;
+    // ---- S^T = K Q^T : two tiles of 32 keys x 32 rows
+    f32x16 s[2];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) s[j] = 0.0f;
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) {
-      const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&s_k[n * KPITCH + kk * 16 + hi * 8]));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s, 0, 0, 0);
-    }
-
-    // register j of this lane is key t0 + 8*(j/4) + 4*hi + j%4 of its row
-    float z[16];
+      for (int j = 0; j < 16; ++j) s[u][j] = 0.0f;
+      const int row = 32 * u + n;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) z[j] = s[j] * a.scale_log2;
-    if (t0 + kChunkTokens - 1 > L + row0) {          // chunk reaches the causal edge of some row
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int t = t0 + 8 * (j >> 2) + 4 * hi + (j & 3);
-        if (t > pos) z[j] = -INFINITY;
+      for (int kk = 0; kk < NK; ++kk) {
+        const int slot = (2 * kk + hi) ^ (row & 15);
+        const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&s_k[st][row * D + slot * 8]));
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s[u], 0, 0, 0);
       }
     }
 
-    float mx = z[0];
+    // register j of tile u is key t0 + 32u + 8*(j/4) + 4*hi + j%4 of this lane's row
+    if (t0 + kChunkTokens - 1 > L + row0) {          // chunk reaches the causal edge of some row
 #pragma unroll
-    for (int j = 1; j < 16; ++j) mx = fmaxf(mx, z[j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int t = t0 + 32 * u + 8 * (j >> 2) + 4 * hi + (j & 3);
+          if (t > pos) s[u][j] = -INFINITY;
+        }
+    }
+
+    float mx = s[0][0];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[u][j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * a.scale_log2;     // scale > 0: max commutes with it
     if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazyMaxSlack) != 0) {
       const float m_new = fmaxf(m_ref, mx);
       const float shrink = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -198,26 +224,36 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
       m_ref = m_new;
     }
 
-    float p[16];
+    // ---- p = 2^(s*scale - m), packed to bf16 in the B-operand order of P^T
+    u32x4 pw[kChunkBlocks];
+    const float neg_m = -m_ref;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      p[j] = __builtin_amdgcn_exp2f(z[j] - m_ref);
-      l_sum += p[j];
+    for (int u = 0; u < 2; ++u) {
+      float p[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        p[j] = __builtin_amdgcn_exp2f(fmaf(s[u][j], a.scale_log2, neg_m));
+        l_sum += p[j];
+      }
+#pragma unroll
+      for (int half_u = 0; half_u < 2; ++half_u) {
+        u32x4 w;
+        w.x = pack_bf16(p[8 * half_u + 0], p[8 * half_u + 1]);
+        w.y = pack_bf16(p[8 * half_u + 2], p[8 * half_u + 3]);
+        w.z = pack_bf16(p[8 * half_u + 4], p[8 * half_u + 5]);
+        w.w = pack_bf16(p[8 * half_u + 6], p[8 * half_u + 7]);
+        pw[2 * u + half_u] = w;
+      }
     }
 
-    // ---- O^T += V^T P^T : two 16-key steps, NMT tiles of 32 head-dim rows
+    // ---- O^T += V^T P^T : one 16-key step per block, NMT tiles of 32 head-dim rows
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      u32x4 pw;
-      pw.x = pack_bf16_rne(p[8 * st + 0], p[8 * st + 1]);
-      pw.y = pack_bf16_rne(p[8 * st + 2], p[8 * st + 3]);
-      pw.z = pack_bf16_rne(p[8 * st + 4], p[8 * st + 5]);
-      pw.w = pack_bf16_rne(p[8 * st + 6], p[8 * st + 7]);
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+    for (int x = 0; x < kChunkBlocks; ++x) {
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[x]);
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt) {
         const bf16x8 va = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st * kTileElems + (mt * 32 + n) * kBlockTokens + hi * 8]));
+            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st][x * kTileElems + (mt * 32 + n) * kBlockTokens + hi * 8]));
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[mt], 0, 0, 0);
       }
     }
@@ -233,10 +269,8 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
 #pragma unroll
       for (int jq = 0; jq < 4; ++jq) {
         u32x2 w;
-        w.x = static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 0] * inv)) |
-              (static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 1] * inv)) << 16);
-        w.y = static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 2] * inv)) |
-              (static_cast<uint32_t>(f32_to_bf16_rne(o[mt][4 * jq + 3] * inv)) << 16);
+        w.x = pack_bf16(o[mt][4 * jq + 0] * inv, o[mt][4 * jq + 1] * inv);
+        w.y = pack_bf16(o[mt][4 * jq + 2] * inv, o[mt][4 * jq + 3] * inv);
         *reinterpret_cast<u32x2*>(op + mt * 32 + 8 * jq + 4 * hi) = w;
       }
     if (a.lse != nullptr && hi == 0)
