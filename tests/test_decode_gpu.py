@@ -197,3 +197,41 @@ def test_full_size_workloads_sampled(cfg):
     assert_lse_close(got_lse, ref_lse, f"workload {cfg} lse")
     # property that holds at any size: sum_t w_t = 1, so |out| never exceeds max |V| (~6 for N(0,1) draws)
     assert np.abs(out).max() < 8.0
+
+
+def test_maximum_context_single_trajectory():
+    """One trajectory at the supported maximum (131 072 tokens, 8 192 blocks) next to minimal ones:
+    the plan cuts it into many items; sampled heads are compared with the oracle."""
+    lens = [131072, 1, 16, 131071]
+    c = small(19, lens, 8, 2, 128)
+    dc = DeviceCase(c)
+    out, lse = dc.decode()
+    assert np.isfinite(out).all()
+    pairs = [(0, 0), (0, 7), (1, 3), (2, 5), (3, 1), (3, 6)]
+    ref, ref_lse, spread = oa.decode_rows(c["pool"], c["row_off"], c["block_ids"], c["lens"], c["q"], 2, pairs,
+                                          with_spread=True)
+    assert_close(np.array([out[b, j] for b, j in pairs]), ref, "max context", spread)
+    assert_lse_close(np.array([lse[b, j] for b, j in pairs]), ref_lse, "max context lse")
+
+
+def test_many_short_trajectories():
+    rng = np.random.default_rng(21)
+    lens = rng.integers(1, 40, 700).tolist()
+    c = small(20, lens, 4, 2, 64)
+    out, lse = DeviceCase(c).decode()
+    ref, ref_lse, spread = oracle_decode(c)
+    assert_close(out, ref, "many short", spread)
+    assert_lse_close(lse, ref_lse, "many short lse")
+
+
+def test_dominant_logits_and_large_values():
+    """Keys scaled so that logits span hundreds of units: the lazily moved maximum must keep
+    every exponent in range, whatever block the largest logit sits in."""
+    lens = [300, 77]
+    c = small(22, lens, 8, 2, 128, poison=False)
+    kf = bits_to_f64(hw.k_view(c["pool"])).astype(np.float32) * 16.0
+    hw.k_view(c["pool"])[:] = hw.f32_to_bf16_bits(kf)
+    out, lse = DeviceCase(c).decode()
+    ref, ref_lse, spread = oracle_decode(c)
+    assert_close(out, ref, "dominant logits", spread)
+    assert np.abs(lse - ref_lse).max() < 1e-3 * np.maximum(1.0, np.abs(ref_lse)).max()
