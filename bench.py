@@ -7,7 +7,7 @@ on the Qwen3-8B-shaped long-tail workload (64 trajectories, 32 query / 8 kv head
 head_dim 128, lognormal context lengths).  Inputs are synthetic and resident in HBM
 before the timed region.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4|5] [--seed S]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4|5] [--op attention|pack] [--seed S]
 """
 from __future__ import annotations
 
@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--op", default="attention", choices=["attention", "pack"],
+                    help="attention: the workload's decode or append pass (default); pack: gather of every "
+                         "trajectory's blocks into one contiguous staging buffer (whole-block copy)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
@@ -68,7 +71,19 @@ def main():
     # synchronisation with every other stream of the process
     stream = torch.cuda.Stream()
 
-    if w.kind == "decode":
+    kind = "pack" if args.op == "pack" else w.kind
+    if kind == "pack":
+        used = np.concatenate([case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]]
+                               for b in range(w.B)]).astype(np.int32)
+        block_elems = w.n_kv_heads * 2 * 16 * w.head_dim
+        staging = torch.empty((len(used), block_elems), dtype=torch.bfloat16, device="cuda")
+        unit_bytes = 2 * len(used) * block_elems * 2          # every byte is read once and written once
+
+        def step():
+            ctx.kv_pack(used, staging, stream=stream)
+
+        dominant, bound = 4, "hbm"
+    elif kind == "decode":
         lens = case["lens"]
         unit_bytes = hw.kv_bytes(lens, w.n_kv_heads, w.head_dim)   # algorithmic bytes of one step
 
@@ -108,11 +123,18 @@ def main():
     t1 = time.perf_counter()
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
-    aux_us = ctx.timing_read(1)[0] if w.kind == "decode" else ctx.timing_read(3)[0]
+    aux_us = ctx.timing_read({"decode": 1, "append": 3, "pack": 5}[kind])[0]
     ctx.timing_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    if w.kind == "decode":
+    if kind == "pack":
+        value = unit_bytes / (ms_per_step * 1e-3) / 1e9
+        metric, unit = "kv-pack read+write GB/s", "GB/s"
+        achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
+        roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "kernel": "kv_move_kernel", "kernel_avg_us": round(kernel_us, 2), "launches_timed": n_launch}
+    elif kind == "decode":
         value = unit_bytes / (ms_per_step * 1e-3) / 1e9
         metric, unit = "decode-attention KV GB/s", "GB/s"
         achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
@@ -157,7 +179,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name} (config {w.cfg_id}, seed {args.seed})", "trajectories": w.B,
+        "config": {"workload": f"{w.name}{' / kv-pack' if kind == 'pack' else ''} (config {w.cfg_id}, seed {args.seed})",
+                   "trajectories": w.B,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "kv_bytes_per_step": unit_bytes, "tokens": int(np.asarray(case["lens"], dtype=np.int64).sum())},
         "us_per_step": round(ms_per_step * 1e3, 1),
@@ -167,11 +190,12 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case, w, np)
+        result["cpu_baseline"] = cpu_baseline(case, w, np, kind)
     print(json.dumps(result))
 
 
-KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_attn_kernel": "append_kernels.hip"}
+KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_attn_kernel": "append_kernels.hip",
+                  "kv_move_kernel": "misc_kernels.hip"}
 
 
 def recorded_traffic(w, kernel):
@@ -195,8 +219,8 @@ def recorded_traffic(w, kernel):
     return int(m.group(1))
 
 
-def cpu_baseline(case, w, np):
-    """The float64 oracle as it stands, timed on this host on a bounded sample."""
+def cpu_baseline(case, w, np, kind):
+    """The oracle as it stands, timed on this host on a bounded sample."""
     from oracle import attention as oa
     try:
         from threadpoolctl import threadpool_info
@@ -205,7 +229,16 @@ def cpu_baseline(case, w, np):
         blas_threads = 1
     budget_s = 20.0
     t0 = time.perf_counter()
-    if w.kind == "decode":
+    if kind == "pack":
+        lens = (case["lens"].astype(np.int64) + (case["chunk_lens"] if "chunk_lens" in case else 0))
+        moved = 0
+        for b in range(len(lens)):
+            moved += 2 * oa.pack(case["pool"], case["row_off"], case["block_ids"], b, int(lens[b])).nbytes
+        dt = time.perf_counter() - t0
+        return {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "sample": f"all {len(lens)} trajectories ({moved} bytes read+written in {dt:.2f} s)",
+                "host_cpus": os.cpu_count(), "affinity": len(os.sched_getaffinity(0))}
+    if kind == "decode":
         lens = case["lens"]
         done_bytes, n_done = 0, 0
         for b in range(len(lens)):

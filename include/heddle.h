@@ -180,6 +180,21 @@ typedef struct heddle_append_args {
 } heddle_append_args;
 int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream);
 
+/* ---- pack / unpack: a trajectory's cache as one contiguous buffer -----------
+ * Staging form of a cache that leaves the pool or enters it: a preempted
+ * trajectory keeps its cache for its next step (Sec. 4.2), a trajectory that is
+ * reassigned moves its cache to the worker that takes it (Sec. 5.3).  pack
+ * copies the n pool blocks block_ids[0..n), in that order, into staging
+ * (DEVICE, n * block_bytes, block_bytes = n_kv_heads * 2 * 16 * head_dim * 2);
+ * unpack copies staging block i into pool block block_ids[i] (ids distinct).
+ * Whole blocks move bit for bit, the slots past the trajectory's length
+ * included.  block_ids is a HOST array, read before the call returns.
+ * Errors: an id outside [0, n_blocks), a repeated id in unpack, n < 0 or a NULL
+ * pointer with n > 0 -> INVAL; a context without a device -> UNSUPPORTED. */
+int heddle_kv_pack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, void* staging, void* hip_stream);
+int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, const void* staging,
+                     void* hip_stream);
+
 /* ---- measurement aids ---------------------------------------------------------
  * Average duration in microseconds of the dominant kernel of the last
  * `heddle_attn_decode` / `heddle_attn_append` calls, measured with HIP events
@@ -188,7 +203,8 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
  * records every N-th launch of each kernel (each recorded launch costs two
  * event records, a few microseconds of stream time); 0 turns it off.
  * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
- * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write. */
+ * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write,
+ * 4 = pack, 5 = unpack. */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
 int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
 

@@ -87,6 +87,8 @@ lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
 lib.heddle_attn_decode.argtypes = [vp, C.POINTER(DecodeArgs), vp]
 lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
+lib.heddle_kv_pack.argtypes = [vp, C.c_int32, i32p, vp, vp]
+lib.heddle_kv_unpack.argtypes = [vp, C.c_int32, i32p, vp, vp]
 lib.heddle_timing_enable.argtypes = [vp, C.c_int32]
 lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
@@ -95,7 +97,8 @@ lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
-           "heddle_attn_append", "heddle_timing_enable", "heddle_timing_read", "heddle_stream_read",
+           "heddle_attn_append", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
+           "heddle_timing_read", "heddle_stream_read",
            "heddle_version"):
     getattr(lib, _f).restype = C.c_int
 
@@ -221,6 +224,15 @@ class Context:
         args = AppendArgs(L.shape[0], Lp, cup, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
                           _dptr(k), _dptr(v), _dptr(out), _dptr(lse))
         _check(lib.heddle_attn_append(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_append")
+
+    # ---- pack / unpack
+    def kv_pack(self, block_ids, staging, stream=None) -> None:
+        a, p = _i32(block_ids)
+        _check(lib.heddle_kv_pack(self._h, a.shape[0], p, _dptr(staging), _stream_ptr(stream)), "heddle_kv_pack")
+
+    def kv_unpack(self, block_ids, staging, stream=None) -> None:
+        a, p = _i32(block_ids)
+        _check(lib.heddle_kv_unpack(self._h, a.shape[0], p, _dptr(staging), _stream_ptr(stream)), "heddle_kv_unpack")
 
     # ---- measurement
     def timing_enable(self, every: int = 1) -> None:

@@ -16,7 +16,7 @@ using namespace heddle;
 namespace {
 
 constexpr int kStagingSlots = 8;
-constexpr int kTimedKernels = 4;       // split-K decode, combine, append, kv write
+constexpr int kTimedKernels = 6;       // split-K decode, combine, append, kv write, pack, unpack
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
 
 struct StagingSlot {
@@ -503,6 +503,45 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
     HEDDLE_HIP(launch_append_attn(al, stream));
   }
   return HEDDLE_OK;
+}
+
+static int kv_move(heddle_ctx* ctx, bool pack, int32_t n, const int32_t* block_ids_host, void* staging,
+                   void* hip_stream) {
+  if (ctx == nullptr || n < 0 || (n > 0 && (block_ids_host == nullptr || staging == nullptr))) return HEDDLE_E_INVAL;
+  const int64_t block_bytes =
+      static_cast<int64_t>(ctx->cfg.n_kv_heads) * 2 * HEDDLE_BLOCK_TOKENS * ctx->cfg.head_dim * 2;
+  for (int32_t i = 0; i < n; ++i)
+    if (block_ids_host[i] < 0 || block_ids_host[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
+  if (!pack) {   // two staged blocks must not land in the same pool block
+    std::vector<uint8_t> seen(static_cast<size_t>(ctx->cfg.n_blocks), 0);
+    for (int32_t i = 0; i < n; ++i) {
+      if (seen[block_ids_host[i]]) return HEDDLE_E_INVAL;
+      seen[block_ids_host[i]] = 1;
+    }
+  }
+  if (!ctx->has_device || block_bytes % 4096 != 0) return HEDDLE_E_UNSUPPORTED;
+  if (n == 0) return HEDDLE_OK;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  StagingSlot* slot = nullptr;
+  int rc = acquire_slot(ctx, static_cast<size_t>(n), &slot);
+  if (rc != HEDDLE_OK) return rc;
+  std::memcpy(slot->host, block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
+  rc = upload(ctx, slot, static_cast<size_t>(n), stream);
+  if (rc != HEDDLE_OK) return rc;
+  TimedScope t(ctx, pack ? 4 : 5, stream);
+  HEDDLE_HIP(launch_kv_move(pack, ctx->cfg.kv_pool, staging, ctx->dev_plan, n, block_bytes, stream));
+  return HEDDLE_OK;
+}
+
+int heddle_kv_pack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, void* staging, void* hip_stream) {
+  return kv_move(ctx, true, n, block_ids_host, staging, hip_stream);
+}
+
+int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, const void* staging,
+                     void* hip_stream) {
+  return kv_move(ctx, false, n, block_ids_host, const_cast<void*>(staging), hip_stream);
 }
 
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {

@@ -81,6 +81,11 @@ bool append_shape_supported(int32_t group, int32_t head_dim);
 int32_t append_tile_rows(int32_t group);   // chunk rows per workgroup tile
 hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream);
 
+// Copies n whole blocks pool[ids[i]] -> staging[i] (pack) or staging[i] -> pool[ids[i]] (unpack);
+// ids is a device array, block_bytes a multiple of 4096.
+hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* ids, int32_t n, int64_t block_bytes,
+                          hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
 
 }  // namespace heddle

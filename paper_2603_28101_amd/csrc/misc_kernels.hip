@@ -1,4 +1,5 @@
-// Small data-movement kernels: scatter of new K/V rows into the paged pool, and a plain
+// Small data-movement kernels: scatter of new K/V rows into the paged pool, whole-block
+// gather / scatter between the pool and a contiguous staging buffer, and a plain
 // streaming read used to measure what the memory system can deliver.
 #include "kernels.h"
 
@@ -44,6 +45,24 @@ __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
   }
 }
 
+// Gathers whole blocks of the pool into a contiguous staging buffer (PACK) or scatters them
+// back under a list of physical blocks.  One workgroup moves one 4 KB slice of a block, one
+// 16-byte non-temporal load and store per thread.
+template <bool PACK>
+__global__ __launch_bounds__(256) void kv_move_kernel(uint16_t* pool, uint16_t* staging, const int32_t* ids,
+                                                       int32_t slices_per_block) {
+  const int i = blockIdx.x / slices_per_block;   // index into ids and into staging
+  const int slice = blockIdx.x - i * slices_per_block;
+  const int64_t block_elems = static_cast<int64_t>(slices_per_block) * 2048;   // 4 KB = 2048 bf16
+  const int64_t off = slice * 2048 + threadIdx.x * 8;
+  u32x4* p = reinterpret_cast<u32x4*>(pool + static_cast<int64_t>(ids[i]) * block_elems + off);
+  u32x4* s = reinterpret_cast<u32x4*>(staging + static_cast<int64_t>(i) * block_elems + off);
+  if (PACK)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(p), s);
+  else
+    __builtin_nontemporal_store(__builtin_nontemporal_load(s), p);
+}
+
 constexpr int kStreamGroups = 2048;
 constexpr int kStreamUnroll = 8;
 
@@ -80,6 +99,20 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, uint
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream) {
   if (a.n_rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(kv_write_kernel, dim3(static_cast<unsigned>(a.n_rows)), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* ids, int32_t n, int64_t block_bytes,
+                          hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int32_t slices = static_cast<int32_t>(block_bytes / 4096);
+  const dim3 grid(static_cast<unsigned>(n) * static_cast<unsigned>(slices));
+  if (pack)
+    hipLaunchKernelGGL(kv_move_kernel<true>, grid, dim3(256), 0, stream, static_cast<uint16_t*>(pool),
+                       static_cast<uint16_t*>(staging), ids, slices);
+  else
+    hipLaunchKernelGGL(kv_move_kernel<false>, grid, dim3(256), 0, stream, static_cast<uint16_t*>(pool),
+                       static_cast<uint16_t*>(staging), ids, slices);
   return hipGetLastError();
 }
 

@@ -1,0 +1,108 @@
+"""GPU parity of heddle_kv_pack / heddle_kv_unpack with the oracle's pack / unpack: byte work,
+so every comparison is bit-exact.  (Staging form of a trajectory's cache, Sec. 4.2 / Sec. 5.3.)"""
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+from oracle import attention as oa
+from tests.gpu_util import DeviceCase, bf16_to_host_bits, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed=3, lens=(700, 1, 16, 17, 4095, 33), n_q=8, n_kv=2, d=128):
+    return hw.build_case(entropy=[7, seed], lens=np.asarray(lens, dtype=np.int32), n_q_heads=n_q,
+                         n_kv_heads=n_kv, head_dim=d, threads=4)
+
+
+def _staging(n_blocks, case):
+    torch = torch_mod()
+    per_block = case["n_kv_heads"] * 2 * 16 * case["head_dim"]
+    return torch.full((max(n_blocks, 1), per_block), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+
+
+@pytest.mark.parametrize("n_kv,d", [(2, 128), (1, 64), (8, 128), (4, 64)])
+def test_pack_matches_oracle(n_kv, d):
+    case = _case(seed=5 + n_kv, n_q=n_kv * 2, n_kv=n_kv, d=d)
+    dc = DeviceCase(case)
+    for b, L in enumerate(case["lens"]):
+        ref = oa.pack(case["pool"], case["row_off"], case["block_ids"], b, int(L))
+        ids = case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]][: ref.shape[0]]
+        st = _staging(ref.shape[0], case)
+        dc.ctx.kv_pack(ids, st)
+        torch_mod().cuda.synchronize()
+        got = bf16_to_host_bits(st)[: ref.shape[0]].reshape(ref.shape)
+        assert np.array_equal(got, ref), f"trajectory {b} (length {L})"
+
+
+def test_unpack_under_other_blocks_then_decode():
+    """Pack every trajectory, unpack under a fresh random assignment of blocks into a second
+    pool, and the pool bytes equal the oracle's unpack; decoding over the moved caches gives the
+    same bits as over the originals."""
+    case = _case(seed=11)
+    dc = DeviceCase(case)
+    out0, lse0 = dc.decode()
+    rng = np.random.default_rng(2)
+    nb = case["n_blocks"]
+    ref_pool = np.full_like(case["pool"], 0x7FC0)            # destination pool starts as NaN patterns
+    torch = torch_mod()
+    moved = DeviceCase({**case, "pool": ref_pool.copy()})
+    perm = rng.permutation(nb).astype(np.int32)
+    new_ids, cursor = np.empty_like(case["block_ids"]), 0
+    for b, L in enumerate(case["lens"]):
+        lo, hi = int(case["row_off"][b]), int(case["row_off"][b + 1])
+        staged_ref = oa.pack(case["pool"], case["row_off"], case["block_ids"], b, int(L))
+        n = staged_ref.shape[0]
+        dst = perm[cursor:cursor + (hi - lo)]
+        cursor += hi - lo
+        new_ids[lo:hi] = dst
+        oa.unpack(ref_pool, dst[:n], staged_ref)
+        st = _staging(n, case)
+        dc.ctx.kv_pack(case["block_ids"][lo:lo + n], st)
+        moved.ctx.kv_unpack(dst[:n], st)
+    torch.cuda.synchronize()
+    got_pool = bf16_to_host_bits(moved.pool).reshape(ref_pool.shape)
+    assert np.array_equal(got_pool, ref_pool)
+    from tests.gpu_util import to_dev_i32
+    moved.block_ids = to_dev_i32(new_ids)
+    out1, lse1 = moved.decode()
+    assert np.array_equal(out0, out1) and np.array_equal(lse0, lse1)
+
+
+def test_roundtrip_whole_workload_shape():
+    """All blocks of the small long-tail workload in one call each way."""
+    case = hw.make_workload(1, seed=0)
+    dc = DeviceCase(case)
+    used = np.concatenate([case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]]
+                           for b in range(len(case["lens"]))]).astype(np.int32)
+    st = _staging(len(used), case)
+    dc.ctx.kv_pack(used, st)
+    torch = torch_mod()
+    torch.cuda.synchronize()
+    got = bf16_to_host_bits(st).reshape((len(used),) + case["pool"].shape[1:])
+    assert np.array_equal(got, case["pool"][used])
+    dc.pool.view(torch.int16).zero_()
+    dc.ctx.kv_unpack(used, st)
+    torch.cuda.synchronize()
+    back = bf16_to_host_bits(dc.pool).reshape(case["pool"].shape)
+    assert np.array_equal(back[used], case["pool"][used])
+    untouched = np.setdiff1d(np.arange(case["n_blocks"]), used)
+    assert not back[untouched].any()
+
+
+def test_empty_and_errors():
+    import paper_2603_28101_amd as heddle
+    case = _case(seed=1, lens=(40,))
+    dc = DeviceCase(case)
+    st = _staging(4, case)
+    before = bf16_to_host_bits(st).copy()
+    dc.ctx.kv_pack(np.zeros(0, dtype=np.int32), st)
+    dc.ctx.kv_unpack(np.zeros(0, dtype=np.int32), st)
+    torch_mod().cuda.synchronize()
+    assert np.array_equal(bf16_to_host_bits(st), before)
+    with pytest.raises(heddle.HeddleError):
+        dc.ctx.kv_pack(np.array([case["n_blocks"]], dtype=np.int32), st)
+    with pytest.raises(heddle.HeddleError):
+        dc.ctx.kv_pack(np.array([-1], dtype=np.int32), st)
+    with pytest.raises(heddle.HeddleError):
+        dc.ctx.kv_unpack(np.array([1, 1], dtype=np.int32), st)
