@@ -45,7 +45,10 @@ WORKLOADS = {
     3: Workload(3, "qwen3-32b-tp4-decode", "decode", 128, 16, 2, 128),
     4: Workload(4, "straggler-decode", "decode", 256, 32, 8, 128),
     5: Workload(5, "tool-append", "append", 32, 32, 8, 128),
+    6: Workload(6, "grpo-group-decode", "decode", 128, 32, 8, 128),
 }
+
+GROUP_SAMPLES = 16   # samples per prompt (Sec. 7, Workloads)
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -90,7 +93,24 @@ def draw_lengths(cfg_id: int, rng: np.random.Generator):
         L = _lognormal_lengths(rng, 32, 8192, 1.0, 1024, 65536)
         C = rng.integers(64, 1025, 32).astype(np.int64)
         return L, C
+    if cfg_id == 6:
+        return draw_group_lengths(rng)[0], None
     raise ValueError(f"unknown workload {cfg_id}")
+
+
+def draw_group_lengths(rng: np.random.Generator):
+    """Workload 6: 8 prompts x 16 samples.  Every sample of a prompt starts with the prompt's
+    tokens (whole blocks of them are shared physically), then continues on its own.
+    Returns (lens[128], group_of[128], prompt_tokens[8]); the batch order is a random
+    interleaving of the samples."""
+    n_prompts = 8
+    prompt = _lognormal_lengths(rng, n_prompts, 2048, 0.6, 256, 8192)
+    own = _lognormal_lengths(rng, n_prompts * GROUP_SAMPLES, 4096, 1.0, 17, 32768)
+    group_of = np.repeat(np.arange(n_prompts), GROUP_SAMPLES)
+    order = rng.permutation(n_prompts * GROUP_SAMPLES)
+    group_of = group_of[order]
+    lens = prompt[group_of] + own[order]
+    return lens.astype(np.int64), group_of.astype(np.int64), prompt
 
 
 def _bf16_normal(rng, shape):
@@ -135,8 +155,15 @@ def build_case(
     permute: bool = True,
     rng: np.random.Generator | None = None,
     threads: int = 8,
+    group_of=None,
+    shared_blocks=None,
 ):
     """Assemble one batch.
+
+    group_of, shared_blocks  optional prefix sharing: trajectory b belongs to group group_of[b]
+                (-1: none) and the first shared_blocks[g] entries of the block-table rows of
+                all members of group g name the same physical blocks.  A shared block must lie
+                wholly below every member's retained length.
 
     lens        tokens already held in the paged pool per trajectory.
     chunk_lens  if given, tokens to be appended per trajectory; the block
@@ -168,10 +195,36 @@ def build_case(
     n_ref = int(row_off[-1])
     n_blocks = max(int(math.ceil(n_ref * overprovision)), n_ref, 1)
 
-    if permute:
-        block_ids = rng.permutation(n_blocks)[:n_ref].astype(np.int32)
+    if group_of is None:
+        if permute:
+            block_ids = rng.permutation(n_blocks)[:n_ref].astype(np.int32)
+        else:
+            block_ids = np.arange(n_ref, dtype=np.int32)
     else:
-        block_ids = np.arange(n_ref, dtype=np.int32)
+        group_of = np.asarray(group_of, dtype=np.int64)
+        shared_blocks = np.asarray(shared_blocks, dtype=np.int64)
+        own_blk = nblk.copy()
+        for b in range(B):
+            if group_of[b] >= 0:
+                p = int(shared_blocks[group_of[b]])
+                if p * BLOCK_TOKENS > lens[b]:
+                    raise ValueError("a shared block must lie below the retained length")
+                own_blk[b] -= p
+        n_unique = int(shared_blocks.sum() + own_blk.sum())
+        n_blocks = max(int(math.ceil(n_unique * overprovision)), n_unique, 1)
+        phys = rng.permutation(n_blocks)[:n_unique] if permute else np.arange(n_unique)
+        g_off = np.concatenate([[0], np.cumsum(shared_blocks)])
+        cursor = int(g_off[-1])
+        block_ids = np.empty(n_ref, dtype=np.int32)
+        for b in range(B):
+            lo = int(row_off[b])
+            p = 0
+            if group_of[b] >= 0:
+                g = int(group_of[b])
+                p = int(shared_blocks[g])
+                block_ids[lo:lo + p] = phys[g_off[g]:g_off[g] + p]
+            block_ids[lo + p:lo + int(nblk[b])] = phys[cursor:cursor + int(own_blk[b])]
+            cursor += int(own_blk[b])
 
     n_rows = B if chunk_lens is None else int(chunk_lens.sum())
     q = _bf16_normal(rng, (n_rows, n_q_heads, head_dim))
@@ -226,7 +279,13 @@ def make_workload(cfg_id: int, seed: int = 0, *, threads: int = 8, **kw):
     draw order: lengths, chunk lengths, block permutation, Q, chunk K/V, pool."""
     w = WORKLOADS[cfg_id]
     rng = np.random.default_rng([cfg_id, seed])
-    lens, chunk = draw_lengths(cfg_id, rng)
+    if cfg_id == 6:
+        lens, group_of, prompt = draw_group_lengths(rng)
+        chunk = None
+        # whole prompt blocks are shared; a prompt's last, partly filled block is private
+        kw = dict(kw, group_of=group_of, shared_blocks=prompt // BLOCK_TOKENS)
+    else:
+        lens, chunk = draw_lengths(cfg_id, rng)
     case = build_case(
         entropy=[cfg_id, seed],
         lens=lens,
@@ -239,6 +298,9 @@ def make_workload(cfg_id: int, seed: int = 0, *, threads: int = 8, **kw):
         **kw,
     )
     case["workload"] = w
+    if cfg_id == 6:
+        case["group_of"] = group_of.astype(np.int32)
+        case["shared_blocks"] = (prompt // BLOCK_TOKENS).astype(np.int32)
     return case
 
 
@@ -246,6 +308,24 @@ def workload_lengths(cfg_id: int, seed: int = 0):
     """Only the length draws of a named workload (cheap; no pool)."""
     rng = np.random.default_rng([cfg_id, seed])
     return draw_lengths(cfg_id, rng)
+
+
+def unique_kv_tokens(case) -> int:
+    """Tokens of context held in distinct physical blocks: a block that several block-table
+    rows name is counted once (tokens of its first owner)."""
+    seen = set()
+    total = 0
+    for b in range(len(case["lens"])):
+        row = case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]]
+        n = int(case["lens"][b])
+        for i, blk in enumerate(row):
+            t = min(BLOCK_TOKENS, n - i * BLOCK_TOKENS)
+            if t <= 0:
+                break
+            if int(blk) not in seen:
+                seen.add(int(blk))
+                total += t
+    return total
 
 
 def kv_bytes(lens, n_kv_heads: int, head_dim: int) -> int:

@@ -76,6 +76,9 @@ typedef struct heddle_config {
   int32_t tile_blk;       /* [4]  splits start at multiples of this many blocks */
   int32_t max_split;      /* [64] most splits per trajectory */
   float   scale;          /* 0 selects 1/sqrt(head_dim) */
+  /* shared-prefix planner parameters (heddle_plan_decode_shared); 0 selects the default */
+  int32_t min_share_blk;    /* [4] fewest common leading blocks that make two trajectories a group */
+  int32_t group_wg_per_cu;  /* [2] work items wanted per CU for the shared-prefix kernel */
 } heddle_config;
 
 /* Creates a context.  *out is written only on success.  With device >= 0 the
@@ -158,6 +161,59 @@ typedef struct heddle_decode_args {
 } heddle_decode_args;
 int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream);
 
+/* ---- decode with shared prefixes --------------------------------------------
+ * The samples of one prompt (16 per prompt in the paper's rollouts, Sec. 7
+ * "Workloads") start with the same tokens, and a prefix-cache hit (Sec. 2.3,
+ * cache-affinity placement) lets their block-table rows name the same physical
+ * blocks for that prefix.  This variant of the decode step reads such a prefix
+ * once per group instead of once per trajectory; the result is the same
+ * attention, defined by each trajectory's own table row.
+ * Plan rule (integer; extends the rule of heddle_plan_decode):
+ *  1. nblk[b] = ceil(len[b]/16); shareable[b] = (len[b]-1)/16, the blocks wholly
+ *     before the step's own row (the block that row is written to is never shared).
+ *  2. Walking b upwards, the first trajectory with shareable >= 1 whose first block
+ *     id is new leads that id; a later trajectory with the same first id joins the
+ *     leader's group iff lcp >= min_share_blk, lcp = number of leading table entries
+ *     equal to the leader's, capped by both shareable counts.  A group exists iff
+ *     someone joined; prefix p_g = min lcp of the joined; members ascending;
+ *     groups numbered by ascending leader.
+ *  3. chunk from W = sum_b (nblk[b] - prefix[b]) as in heddle_plan_decode; chunk_g
+ *     likewise from Wg = sum_g p_g * ceil(members_g / tile_members) with target_g =
+ *     max(1, n_cu * group_wg_per_cu / n_kv_heads); tile_members = 128 / G.
+ *  4. cut(n, c): ns = min(ceil(n/c), max_split); per = ceil(n/ns) rounded up to
+ *     tile_blk; count = ceil(n/per).
+ *  5. group g: cut(p_g, chunk_g) -> parts k over leader blocks [k*per, min((k+1)*per,
+ *     p_g)), each crossed with member tiles of tile_members consecutive members
+ *     (group items, sorted by (-(blk_end-blk_begin), g, k, tile)).
+ *  6. trajectory b: cut(nblk[b]-prefix[b], chunk) -> parts over [prefix[b] + k*per, ...)
+ *     with slot = parts_g + k; nsplit[b] = parts_g + count; items sorted as before.
+ * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape the
+ * matrix-core kernel does not support (head_dim != 128) no groups are formed. */
+typedef struct heddle_shared_plan {
+  int32_t  cap_items, cap_gitems, cap_groups;          /* in  */
+  int32_t  n_items, n_gitems, n_groups, chunk, chunk_g; /* out */
+  int32_t* item_b;  int32_t* item_s;  int32_t* item_blk_begin;  int32_t* item_blk_end;   /* [n_items]  */
+  int32_t* gitem_g; int32_t* gitem_k; int32_t* gitem_blk_begin; int32_t* gitem_blk_end;  /* [n_gitems] */
+  int32_t* gitem_m0; int32_t* gitem_mn;   /* [n_gitems] members[member_off[g] + m0 .. + mn) */
+  int32_t* group_leader; int32_t* group_prefix; int32_t* group_parts;   /* [n_groups] */
+  int32_t* member_off;       /* [n_groups + 1] */
+  int32_t* members;          /* [B] (member_off[n_groups] used) */
+  int32_t* traj_group;       /* [B] group of the trajectory or -1 */
+  int32_t* traj_prefix;      /* [B] shared blocks of the trajectory (0 outside groups) */
+  int32_t* nsplit;           /* [B] */
+  int32_t* part_off;         /* [B+1] */
+} heddle_shared_plan;
+int heddle_plan_decode_shared(const heddle_ctx* ctx, int32_t B, const int32_t* len_host,
+                              const int32_t* row_off_host, const int32_t* block_ids_host,
+                              heddle_shared_plan* plan);
+
+/* Same arguments, results and errors as heddle_attn_decode, plus the HOST copy of
+ * the block table (block_ids_host [row_off_host[B]], read before the call returns)
+ * from which the groups are found.  Two trajectories may name the same physical
+ * block only in positions wholly below both lengths. */
+int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, const int32_t* block_ids_host,
+                              void* hip_stream);
+
 /* ---- append: a chunk of C_b >= 1 new tokens per trajectory ------------------
  * The chunk's K/V rows are stored at positions L_b .. L_b+C_b-1 (the table must
  * already cover L_b + C_b tokens), then chunk row i attends to positions
@@ -204,7 +260,7 @@ int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, 
  * event records, a few microseconds of stream time); 0 turns it off.
  * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
  * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write,
- * 4 = pack, 5 = unpack. */
+ * 4 = pack, 5 = unpack, 6 = shared-prefix kernel. */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
 int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
 

@@ -62,13 +62,17 @@ def weight_spread(w, V, out, centered=True):
     """Standard deviation of the output under independent unit-variance relative
     perturbations of the weights, to first order.  centered: numerator and denominator are
     perturbed alike, sqrt(sum_t w_t^2 (V[t] - out)^2); otherwise only the numerator is,
-    sqrt(sum_t w_t^2 V[t]^2).  The tests use it to bound what rounding the weights to bf16
-    may do to a result."""
+    sqrt(sum_t w_t^2 V[t]^2); centered=None: some keys one way and the rest the other way,
+    bounded by the root of the sum of both squares.  The tests use it to bound what rounding
+    the weights to bf16 may do to a result."""
+    if centered is None:
+        return np.sqrt((w * w) @ ((V - out) ** 2) + (w * w) @ (V ** 2))
     dev = V - out if centered else V
     return np.sqrt((w * w) @ (dev ** 2))
 
 
-def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=None, with_spread=False):
+def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=None, with_spread=False,
+           centered=True):
     """One new token per trajectory.  q_bits uint16 [B][n_q][d].
     Returns out float64 [B][n_q][d], lse float64 [B][n_q] (and weight_spread [B][n_q][d])."""
     B, n_q, d = q_bits.shape
@@ -85,11 +89,12 @@ def decode(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads: int, scale=N
         for j in range(n_q):
             out[b, j], lse[b, j], w = attend(q[b, j], K[j // G], V[j // G], s)
             if with_spread:
-                spread[b, j] = weight_spread(w, V[j // G], out[b, j])
+                spread[b, j] = weight_spread(w, V[j // G], out[b, j], centered)
     return (out, lse, spread) if with_spread else (out, lse)
 
 
-def decode_rows(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads, pairs, scale=None, with_spread=False):
+def decode_rows(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads, pairs, scale=None, with_spread=False,
+                centered=True):
     """decode() restricted to a list of (b, j) pairs; for sampled checks on
     batches too large to evaluate in full."""
     _, n_q, d = q_bits.shape
@@ -105,7 +110,7 @@ def decode_rows(pool_bits, row_off, block_ids, lens, q_bits, n_kv_heads, pairs, 
         outs.append(o)
         lses.append(l)
         if with_spread:
-            spreads.append(weight_spread(w, V[j // G], o))
+            spreads.append(weight_spread(w, V[j // G], o, centered))
     if with_spread:
         return np.array(outs), np.array(lses), np.array(spreads)
     return np.array(outs), np.array(lses)

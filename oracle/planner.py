@@ -90,3 +90,137 @@ def plan_append(ctx_lens, chunk_lens, tile_rows: int):
         tile_rows_n=i32([t[4] for t in tiles]),
         tile_extent=i32([-t[0] for t in tiles]),
     )
+
+
+def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: int, n_cu=256,
+                       wg_per_cu=4, min_chunk_blk=16, tile_blk=4, max_split=64, min_share_blk=4,
+                       group_wg_per_cu=2):
+    """Split-K plan for a decode step in which trajectories whose block-table rows begin with
+    the same physical blocks (the samples of one prompt, Sec. 7 Workloads; a prefix-cache hit
+    in the sense of Sec. 2.3) read that shared prefix once per group instead of once each.
+
+    Rule (all integer arithmetic; BT = 16):
+      1. nblk[b] = ceil(len[b]/BT); shareable[b] = (len[b]-1) // BT: blocks wholly before the
+         position of the step's own row (the block that row is written to is never shared).
+      2. Walk b upwards.  The first trajectory whose first block id has not been seen is the
+         leader of that id.  For a later trajectory with the same first id, lcp = number of
+         leading table entries equal to the leader's, capped by both shareable counts; it joins
+         the leader's group iff lcp >= min_share_blk.  A group exists iff someone joined; its
+         prefix p = min lcp over the joined; members = leader + joined, ascending b.
+         Groups are numbered by ascending leader.  prefix[b] = p for members, else 0.
+      3. Private work W = sum_b (nblk[b] - prefix[b]); target and chunk from W as in plan_decode.
+         Shared work Wg = sum_g p_g * ceil(|members_g| / tile_members);
+         target_g = max(1, floor(n_cu * group_wg_per_cu / n_kv_heads));
+         chunk_g = max(ceil(Wg / target_g), min_chunk_blk) rounded up to a multiple of tile_blk.
+      4. cut(n, c) -> (per, count): ns = min(ceil(n/c), max_split); per = ceil(n/ns) rounded up
+         to a multiple of tile_blk; count = ceil(n/per).
+      5. Group g: (per, np_g) = cut(p_g, chunk_g); prefix part k covers blocks
+         [k*per, min((k+1)*per, p_g)) of the leader's row.  Members are cut into tiles of
+         tile_members consecutive members.  Group items (g, k, t) carry (blk_begin, blk_end,
+         first member index, member count).
+      6. Trajectory b: n = nblk[b] - prefix[b] (>= 1); (per, ns_b) = cut(n, chunk); suffix part k covers
+         [prefix[b] + k*per, min(prefix[b] + (k+1)*per, nblk[b])) and has slot np_g + k
+         (np_g = 0 outside groups).  nsplit[b] = np_g + ns_b; part_off = exclusive prefix sum.
+      7. decode items sorted by (-(blk_end-blk_begin), b, slot); group items sorted by
+         (-(blk_end-blk_begin), g, k, t).
+    """
+    lens = [int(x) for x in lens]
+    row_off = [int(x) for x in row_off]
+    B = len(lens)
+    nblk = [_ceil_div(n, BLOCK_TOKENS) for n in lens]
+    shareable = [(n - 1) // BLOCK_TOKENS for n in lens]
+
+    leader_of_id, joined, lcp_of = {}, {}, {}
+    for b in range(B):
+        if shareable[b] < 1:
+            continue
+        first = int(block_ids[row_off[b]])
+        if first not in leader_of_id:
+            leader_of_id[first] = b
+            continue
+        a = leader_of_id[first]
+        cap = min(shareable[a], shareable[b])
+        n = 0
+        while n < cap and int(block_ids[row_off[a] + n]) == int(block_ids[row_off[b] + n]):
+            n += 1
+        if n >= min_share_blk:
+            joined.setdefault(a, []).append(b)
+            lcp_of[b] = n
+    leaders = sorted(joined)
+    group_leader, group_prefix, group_members = [], [], []
+    traj_group, prefix = [-1] * B, [0] * B
+    for g, a in enumerate(leaders):
+        p = min(lcp_of[b] for b in joined[a])
+        members = [a] + joined[a]
+        group_leader.append(a)
+        group_prefix.append(p)
+        group_members.append(members)
+        for b in members:
+            traj_group[b], prefix[b] = g, p
+
+    W = sum(nblk[b] - prefix[b] for b in range(B))
+    target = max(1, (n_cu * wg_per_cu) // n_kv_heads)
+    chunk = _round_up(max(_ceil_div(W, target), min_chunk_blk), tile_blk)
+    Wg = sum(p * _ceil_div(len(m), tile_members) for p, m in zip(group_prefix, group_members))
+    target_g = max(1, (n_cu * group_wg_per_cu) // n_kv_heads)
+    chunk_g = _round_up(max(_ceil_div(Wg, target_g), min_chunk_blk), tile_blk)
+
+    def cut(n, c):
+        ns = min(_ceil_div(n, c), max_split)
+        per = _round_up(_ceil_div(n, ns), tile_blk)
+        return per, _ceil_div(n, per)
+
+    gitems, group_parts = [], []
+    for g, p in enumerate(group_prefix):
+        per, cnt = cut(p, chunk_g)
+        group_parts.append(cnt)
+        n_mem = len(group_members[g])
+        for k in range(cnt):
+            lo, hi = k * per, min((k + 1) * per, p)
+            for t in range(_ceil_div(n_mem, tile_members)):
+                m0 = t * tile_members
+                gitems.append((-(hi - lo), g, k, t, lo, hi, m0, min(tile_members, n_mem - m0)))
+    gitems.sort()
+
+    nsplit, part_off, items = [], [0], []
+    for b in range(B):
+        npg = group_parts[traj_group[b]] if traj_group[b] >= 0 else 0
+        n = nblk[b] - prefix[b]
+        per, cnt = cut(n, chunk)
+        nsplit.append(npg + cnt)
+        part_off.append(part_off[-1] + npg + cnt)
+        for k in range(cnt):
+            lo, hi = prefix[b] + k * per, min(prefix[b] + (k + 1) * per, nblk[b])
+            items.append((-(hi - lo), b, npg + k, lo, hi))
+    items.sort()
+
+    i32 = lambda v: np.asarray(v, dtype=np.int32)
+    member_off = [0]
+    for m in group_members:
+        member_off.append(member_off[-1] + len(m))
+    return dict(
+        chunk=chunk,
+        chunk_g=chunk_g,
+        n_groups=len(leaders),
+        group_leader=i32(group_leader),
+        group_prefix=i32(group_prefix),
+        group_parts=i32(group_parts),
+        member_off=i32(member_off),
+        members=i32([b for m in group_members for b in m]),
+        traj_group=i32(traj_group),
+        traj_prefix=i32(prefix),
+        n_items=len(items),
+        item_b=i32([it[1] for it in items]),
+        item_s=i32([it[2] for it in items]),
+        item_blk_begin=i32([it[3] for it in items]),
+        item_blk_end=i32([it[4] for it in items]),
+        n_gitems=len(gitems),
+        gitem_g=i32([it[1] for it in gitems]),
+        gitem_k=i32([it[2] for it in gitems]),
+        gitem_blk_begin=i32([it[4] for it in gitems]),
+        gitem_blk_end=i32([it[5] for it in gitems]),
+        gitem_m0=i32([it[6] for it in gitems]),
+        gitem_mn=i32([it[7] for it in gitems]),
+        nsplit=i32(nsplit),
+        part_off=i32(part_off),
+    )

@@ -42,6 +42,7 @@ class Config(C.Structure):
         ("n_cu", C.c_int32), ("wg_per_cu", C.c_int32), ("min_chunk_blk", C.c_int32),
         ("tile_blk", C.c_int32), ("max_split", C.c_int32),
         ("scale", C.c_float),
+        ("min_share_blk", C.c_int32), ("group_wg_per_cu", C.c_int32),
     ]
 
 
@@ -51,6 +52,21 @@ class Plan(C.Structure):
         ("item_b", i32p), ("item_s", i32p), ("item_blk_begin", i32p), ("item_blk_end", i32p),
         ("nsplit", i32p), ("part_off", i32p),
     ]
+
+
+_SHARED_ITEM = ("item_b", "item_s", "item_blk_begin", "item_blk_end")
+_SHARED_GITEM = ("gitem_g", "gitem_k", "gitem_blk_begin", "gitem_blk_end", "gitem_m0", "gitem_mn")
+_SHARED_GROUP = ("group_leader", "group_prefix", "group_parts")
+_SHARED_TRAJ = ("members", "traj_group", "traj_prefix", "nsplit")
+
+
+class SharedPlan(C.Structure):
+    _fields_ = (
+        [(k, C.c_int32) for k in ("cap_items", "cap_gitems", "cap_groups", "n_items", "n_gitems", "n_groups",
+                                  "chunk", "chunk_g")]
+        + [(k, i32p) for k in _SHARED_ITEM + _SHARED_GITEM + _SHARED_GROUP]
+        + [("member_off", i32p)] + [(k, i32p) for k in _SHARED_TRAJ] + [("part_off", i32p)]
+    )
 
 
 class AppendPlan(C.Structure):
@@ -86,6 +102,8 @@ lib.heddle_kv_num_free.argtypes = [vp, i32p]
 lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
 lib.heddle_attn_decode.argtypes = [vp, C.POINTER(DecodeArgs), vp]
+lib.heddle_plan_decode_shared.argtypes = [vp, C.c_int32, i32p, i32p, i32p, C.POINTER(SharedPlan)]
+lib.heddle_attn_decode_shared.argtypes = [vp, C.POINTER(DecodeArgs), i32p, vp]
 lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
 lib.heddle_kv_pack.argtypes = [vp, C.c_int32, i32p, vp, vp]
 lib.heddle_kv_unpack.argtypes = [vp, C.c_int32, i32p, vp, vp]
@@ -97,7 +115,7 @@ lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
-           "heddle_attn_append", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
+           "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
            "heddle_timing_read", "heddle_stream_read",
            "heddle_version"):
     getattr(lib, _f).restype = C.c_int
@@ -144,9 +162,11 @@ class Context:
     """One paged KV pool with its block manager, planners and attention calls."""
 
     def __init__(self, n_q_heads, n_kv_heads, head_dim, n_blocks, kv_pool=None, device=-1, *,
-                 n_cu=0, wg_per_cu=0, min_chunk_blk=0, tile_blk=0, max_split=0, scale=0.0):
+                 n_cu=0, wg_per_cu=0, min_chunk_blk=0, tile_blk=0, max_split=0, scale=0.0,
+                 min_share_blk=0, group_wg_per_cu=0):
         self.cfg = Config(n_q_heads, n_kv_heads, head_dim, 16, n_blocks, device, _dptr(kv_pool),
-                          n_cu, wg_per_cu, min_chunk_blk, tile_blk, max_split, scale)
+                          n_cu, wg_per_cu, min_chunk_blk, tile_blk, max_split, scale,
+                          min_share_blk, group_wg_per_cu)
         self._pool = kv_pool  # keep the tensor alive
         self._h = vp()
         _check(lib.heddle_ctx_create(C.byref(self.cfg), C.byref(self._h)), "heddle_ctx_create")
@@ -193,6 +213,36 @@ class Context:
         out.update(n_items=p.n_items, chunk=p.chunk, nsplit=nsplit, part_off=part_off)
         return out
 
+    def plan_decode_shared(self, lens, row_off, block_ids) -> dict:
+        lens_a, lens_p = _i32(lens)
+        ro_a, ro_p = _i32(row_off)
+        ids_a, ids_p = _i32(block_ids)
+        B = lens_a.shape[0]
+        cap_items = max(B * self.max_split, 1)
+        cap_gitems = max(B * self.max_split, 1)
+        cap_groups = max(B // 2, 1)
+        arrs = {k: np.empty(cap_items, dtype=np.int32) for k in _SHARED_ITEM}
+        arrs.update({k: np.empty(cap_gitems, dtype=np.int32) for k in _SHARED_GITEM})
+        arrs.update({k: np.empty(cap_groups, dtype=np.int32) for k in _SHARED_GROUP})
+        arrs["member_off"] = np.empty(cap_groups + 1, dtype=np.int32)
+        arrs.update({k: np.empty(B, dtype=np.int32) for k in _SHARED_TRAJ})
+        arrs["part_off"] = np.empty(B + 1, dtype=np.int32)
+        p = SharedPlan(cap_items, cap_gitems, cap_groups, 0, 0, 0, 0, 0,
+                       *(arrs[k].ctypes.data_as(i32p) for k in _SHARED_ITEM + _SHARED_GITEM + _SHARED_GROUP),
+                       arrs["member_off"].ctypes.data_as(i32p),
+                       *(arrs[k].ctypes.data_as(i32p) for k in _SHARED_TRAJ),
+                       arrs["part_off"].ctypes.data_as(i32p))
+        _check(lib.heddle_plan_decode_shared(self._h, B, lens_p, ro_p, ids_p, C.byref(p)),
+               "heddle_plan_decode_shared")
+        out = {k: arrs[k][: p.n_items].copy() for k in _SHARED_ITEM}
+        out.update({k: arrs[k][: p.n_gitems].copy() for k in _SHARED_GITEM})
+        out.update({k: arrs[k][: p.n_groups].copy() for k in _SHARED_GROUP})
+        out["member_off"] = arrs["member_off"][: p.n_groups + 1].copy()
+        out["members"] = arrs["members"][: int(out["member_off"][-1])].copy()
+        out.update({k: arrs[k] for k in ("traj_group", "traj_prefix", "nsplit", "part_off")})
+        out.update(n_items=p.n_items, n_gitems=p.n_gitems, n_groups=p.n_groups, chunk=p.chunk, chunk_g=p.chunk_g)
+        return out
+
     def plan_append(self, ctx_lens, cu_chunk, tile_rows: int = 0) -> dict:
         L, Lp = _i32(ctx_lens)
         cu, cup = _i32(cu_chunk)
@@ -215,6 +265,16 @@ class Context:
         args = DecodeArgs(lens_a.shape[0], lens_p, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
                           _dptr(k_new), _dptr(v_new), _dptr(out), _dptr(lse))
         _check(lib.heddle_attn_decode(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_decode")
+
+    def attn_decode_shared(self, lens, row_off_host, block_ids_host, row_off, block_ids, q, out, lse=None,
+                           k_new=None, v_new=None, stream=None) -> None:
+        lens_a, lens_p = _i32(lens)
+        ro_a, ro_p = _i32(row_off_host)
+        ids_a, ids_p = _i32(block_ids_host)
+        args = DecodeArgs(lens_a.shape[0], lens_p, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
+                          _dptr(k_new), _dptr(v_new), _dptr(out), _dptr(lse))
+        _check(lib.heddle_attn_decode_shared(self._h, C.byref(args), ids_p, _stream_ptr(stream)),
+               "heddle_attn_decode_shared")
 
     def attn_append(self, ctx_lens, cu_chunk, row_off_host, row_off, block_ids, q, k, v, out, lse=None,
                     stream=None) -> None:

@@ -16,7 +16,7 @@ using namespace heddle;
 namespace {
 
 constexpr int kStagingSlots = 8;
-constexpr int kTimedKernels = 6;       // split-K decode, combine, append, kv write, pack, unpack
+constexpr int kTimedKernels = 7;       // split-K decode, combine, append, kv write, pack, unpack, shared prefix
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
 
 struct StagingSlot {
@@ -58,6 +58,8 @@ struct heddle_ctx {
   std::vector<DecodeItem> items;
   std::vector<int32_t> nsplit, part_off;
   std::vector<AppendTile> tiles;
+  SharedPlan shared;
+  int32_t min_share_blk = 4, group_wg_per_cu = 2;
 };
 
 namespace {
@@ -175,7 +177,8 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads != 0) return HEDDLE_E_INVAL;
   if (cfg->block_tokens != HEDDLE_BLOCK_TOKENS || cfg->n_blocks < 1) return HEDDLE_E_INVAL;
   if (cfg->head_dim < 8 || cfg->head_dim % 8 != 0) return HEDDLE_E_INVAL;
-  if (cfg->n_cu < 0 || cfg->wg_per_cu < 0 || cfg->min_chunk_blk < 0 || cfg->tile_blk < 0 || cfg->max_split < 0)
+  if (cfg->n_cu < 0 || cfg->wg_per_cu < 0 || cfg->min_chunk_blk < 0 || cfg->tile_blk < 0 || cfg->max_split < 0 ||
+      cfg->min_share_blk < 0 || cfg->group_wg_per_cu < 0)
     return HEDDLE_E_INVAL;
   if (cfg->device < -1 || (cfg->device >= 0 && cfg->kv_pool == nullptr)) return HEDDLE_E_INVAL;
   if (!(cfg->scale >= 0.f) || !std::isfinite(cfg->scale)) return HEDDLE_E_INVAL;
@@ -208,6 +211,8 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   ctx->plan.min_chunk_blk = cfg->min_chunk_blk ? cfg->min_chunk_blk : 16;
   ctx->plan.tile_blk = cfg->tile_blk ? cfg->tile_blk : 4;
   ctx->plan.max_split = cfg->max_split ? cfg->max_split : 64;
+  ctx->min_share_blk = cfg->min_share_blk ? cfg->min_share_blk : 4;
+  ctx->group_wg_per_cu = cfg->group_wg_per_cu ? cfg->group_wg_per_cu : 2;
   *out = ctx.release();
   return HEDDLE_OK;
 }
@@ -301,7 +306,9 @@ int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_
   return HEDDLE_OK;
 }
 
-int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+namespace {
+
+int check_decode_args(const heddle_ctx* ctx, const heddle_decode_args* args) {
   if (ctx == nullptr || args == nullptr) return HEDDLE_E_INVAL;
   if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
   const int32_t B = args->B;
@@ -309,13 +316,228 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
       !args->out)
     return HEDDLE_E_INVAL;
   if ((args->k_new == nullptr) != (args->v_new == nullptr)) return HEDDLE_E_INVAL;
+  if (args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
   for (int32_t b = 0; b < B; ++b) {
     const int32_t n = args->len_host[b];
     if (n < 1 || n > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
     if (args->row_off_host[b + 1] < args->row_off_host[b] || !table_covers(args->row_off_host, b, n))
       return HEDDLE_E_INVAL;
   }
-  if (args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
+  return HEDDLE_OK;
+}
+
+// Group formation of the shared-prefix plan with this context's parameters; on shapes the
+// matrix-core kernel is not built for nobody is grouped.
+void plan_shared_for(const heddle_ctx* ctx, int32_t B, const int32_t* len, const int32_t* row_off,
+                     const int32_t* block_ids, SharedPlan& out) {
+  const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
+  const bool can_group = append_shape_supported(G, ctx->cfg.head_dim);
+  const int32_t tile_members = can_group ? append_tile_rows(G) : 1;
+  plan_decode_shared(ctx->plan, can_group ? ctx->min_share_blk : INT32_MAX, ctx->group_wg_per_cu, tile_members, B,
+                     len, row_off, block_ids, out);
+}
+
+}  // namespace
+
+int heddle_plan_decode_shared(const heddle_ctx* ctx, int32_t B, const int32_t* len_host,
+                              const int32_t* row_off_host, const int32_t* block_ids_host,
+                              heddle_shared_plan* plan) {
+  if (ctx == nullptr || plan == nullptr || !len_host || !row_off_host || !block_ids_host || B < 1)
+    return HEDDLE_E_INVAL;
+  if (!plan->item_b || !plan->item_s || !plan->item_blk_begin || !plan->item_blk_end || !plan->gitem_g ||
+      !plan->gitem_k || !plan->gitem_blk_begin || !plan->gitem_blk_end || !plan->gitem_m0 || !plan->gitem_mn ||
+      !plan->group_leader || !plan->group_prefix || !plan->group_parts || !plan->member_off || !plan->members ||
+      !plan->traj_group || !plan->traj_prefix || !plan->nsplit || !plan->part_off)
+    return HEDDLE_E_INVAL;
+  if (row_off_host[0] < 0) return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b) {
+    if (len_host[b] < 1 || len_host[b] > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+    if (row_off_host[b + 1] < row_off_host[b] || !table_covers(row_off_host, b, len_host[b])) return HEDDLE_E_INVAL;
+  }
+  SharedPlan sp;
+  plan_shared_for(ctx, B, len_host, row_off_host, block_ids_host, sp);
+  const size_t n_groups = sp.group_leader.size();
+  if (static_cast<int64_t>(sp.items.size()) > plan->cap_items ||
+      static_cast<int64_t>(sp.gitems.size()) > plan->cap_gitems || static_cast<int64_t>(n_groups) > plan->cap_groups)
+    return HEDDLE_E_NOMEM;
+  plan->n_items = static_cast<int32_t>(sp.items.size());
+  plan->n_gitems = static_cast<int32_t>(sp.gitems.size());
+  plan->n_groups = static_cast<int32_t>(n_groups);
+  plan->chunk = sp.chunk;
+  plan->chunk_g = sp.chunk_g;
+  for (size_t i = 0; i < sp.items.size(); ++i) {
+    plan->item_b[i] = sp.items[i].b;
+    plan->item_s[i] = sp.items[i].s;
+    plan->item_blk_begin[i] = sp.items[i].blk_begin;
+    plan->item_blk_end[i] = sp.items[i].blk_end;
+  }
+  for (size_t i = 0; i < sp.gitems.size(); ++i) {
+    plan->gitem_g[i] = sp.gitems[i].g;
+    plan->gitem_k[i] = sp.gitems[i].k;
+    plan->gitem_blk_begin[i] = sp.gitems[i].blk_begin;
+    plan->gitem_blk_end[i] = sp.gitems[i].blk_end;
+    plan->gitem_m0[i] = sp.gitems[i].m0;
+    plan->gitem_mn[i] = sp.gitems[i].mn;
+  }
+  auto copy = [](int32_t* dst, const std::vector<int32_t>& v) {
+    if (!v.empty()) std::memcpy(dst, v.data(), sizeof(int32_t) * v.size());
+  };
+  copy(plan->group_leader, sp.group_leader);
+  copy(plan->group_prefix, sp.group_prefix);
+  copy(plan->group_parts, sp.group_parts);
+  copy(plan->member_off, sp.member_off);
+  copy(plan->members, sp.members);
+  copy(plan->traj_group, sp.traj_group);
+  copy(plan->traj_prefix, sp.traj_prefix);
+  copy(plan->nsplit, sp.nsplit);
+  copy(plan->part_off, sp.part_off);
+  return HEDDLE_OK;
+}
+
+int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, const int32_t* block_ids_host,
+                              void* hip_stream) {
+  int rc = check_decode_args(ctx, args);
+  if (rc != HEDDLE_OK) return rc;
+  if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
+  const int32_t B = args->B;
+
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  SharedPlan& sp = ctx->shared;
+  plan_shared_for(ctx, B, args->len_host, args->row_off_host, block_ids_host, sp);
+  const size_t n_items = sp.items.size(), n_gitems = sp.gitems.size(), n_members = sp.members.size();
+  const size_t n_parts = static_cast<size_t>(sp.part_off[B]);
+  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
+
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, n_parts * Hq * D,
+                   sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 4,
+                   sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+
+  // plan image: item records | group item records | trajectory records | first_pos[B] | cu_rows[B+1] | members
+  const size_t nB = static_cast<size_t>(B);
+  const size_t words = 8 * n_items + 8 * n_gitems + 2 * nB + nB + nB + 1 + n_members;
+  StagingSlot* slot = nullptr;
+  rc = acquire_slot(ctx, words, &slot);
+  if (rc != HEDDLE_OK) return rc;
+  int32_t* w = slot->host;
+  DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
+  GroupItemRec* h_gitems = reinterpret_cast<GroupItemRec*>(w + 8 * n_items);
+  DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * (n_items + n_gitems));
+  int32_t* h_first = w + 8 * (n_items + n_gitems) + 2 * nB;
+  int32_t* h_cu = h_first + B;
+  int32_t* h_members = h_cu + B + 1;
+  for (size_t i = 0; i < n_items; ++i) {
+    const DecodeItem& it = sp.items[i];
+    DecodeItemRec& r = h_items[i];
+    r.b = it.b;
+    r.slot = sp.part_off[it.b] + it.s;
+    r.blk_begin = it.blk_begin;
+    r.blk_end = it.blk_end;
+    r.len = args->len_host[it.b];
+    r.table_off = args->row_off_host[it.b];
+    r.nsplit = sp.nsplit[it.b];
+    r.pad = 0;
+  }
+  for (size_t i = 0; i < n_gitems; ++i) {
+    const GroupItem& it = sp.gitems[i];
+    GroupItemRec& r = h_gitems[i];
+    r.table_off = args->row_off_host[sp.group_leader[it.g]];
+    r.blk_begin = it.blk_begin;
+    r.blk_end = it.blk_end;
+    r.part = it.k;
+    r.member_off = sp.member_off[it.g] + it.m0;
+    r.n_members = it.mn;
+    r.pad[0] = r.pad[1] = 0;
+  }
+  for (int32_t b = 0; b < B; ++b) {
+    h_trajs[b].part_off = sp.part_off[b];
+    h_trajs[b].nsplit = sp.nsplit[b];
+    h_first[b] = args->len_host[b] - 1;
+    h_cu[b] = b;
+  }
+  h_cu[B] = B;
+  if (n_members > 0) std::memcpy(h_members, sp.members.data(), sizeof(int32_t) * n_members);
+  rc = upload(ctx, slot, words, stream);
+  if (rc != HEDDLE_OK) return rc;
+  const int32_t* d = ctx->dev_plan;
+  ctx->enqueued = true;
+
+  if (args->k_new != nullptr) {
+    KvWriteLaunch kw{};
+    kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
+    kw.row_off = args->row_off;
+    kw.block_ids = args->block_ids;
+    kw.first_pos = d + (h_first - w);
+    kw.cu_rows = d + (h_cu - w);
+    kw.k = static_cast<const uint16_t*>(args->k_new);
+    kw.v = static_cast<const uint16_t*>(args->v_new);
+    kw.B = B;
+    kw.n_rows = B;
+    kw.n_kv_heads = ctx->cfg.n_kv_heads;
+    kw.head_dim = D;
+    TimedScope t(ctx, 3, stream);
+    HEDDLE_HIP(launch_kv_write(kw, stream));
+  }
+
+  const float scale_log2 = ctx->scale * 1.4426950408889634f;
+  const DecodeTrajRec* d_trajs = reinterpret_cast<const DecodeTrajRec*>(d + 8 * (n_items + n_gitems));
+  if (n_gitems > 0) {
+    GroupLaunch gl{};
+    gl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
+    gl.block_ids = args->block_ids;
+    gl.items = reinterpret_cast<const GroupItemRec*>(d + 8 * n_items);
+    gl.members = d + (h_members - w);
+    gl.trajs = d_trajs;
+    gl.q = static_cast<const uint16_t*>(args->q);
+    gl.part_acc = ctx->dev_part_acc;
+    gl.part_ml = ctx->dev_part_ml;
+    gl.n_items = static_cast<int32_t>(n_gitems);
+    gl.n_q_heads = Hq;
+    gl.n_kv_heads = ctx->cfg.n_kv_heads;
+    gl.head_dim = D;
+    gl.scale_log2 = scale_log2;
+    TimedScope t(ctx, 6, stream);
+    HEDDLE_HIP(launch_group_attn(gl, stream));
+  }
+
+  DecodeLaunch dl{};
+  dl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
+  dl.block_ids = args->block_ids;
+  dl.items = reinterpret_cast<const DecodeItemRec*>(d);
+  dl.trajs = d_trajs;
+  dl.q = static_cast<const uint16_t*>(args->q);
+  dl.part_acc = ctx->dev_part_acc;
+  dl.part_ml = ctx->dev_part_ml;
+  dl.out = static_cast<uint16_t*>(args->out);
+  dl.lse = args->lse;
+  dl.B = B;
+  dl.n_items = static_cast<int32_t>(n_items);
+  dl.n_q_heads = Hq;
+  dl.n_kv_heads = ctx->cfg.n_kv_heads;
+  dl.head_dim = D;
+  dl.scale_log2 = scale_log2;
+  {
+    TimedScope t(ctx, 0, stream);
+    HEDDLE_HIP(launch_decode_splitk(dl, stream));
+  }
+  if (n_parts > nB) {
+    TimedScope t(ctx, 1, stream);
+    HEDDLE_HIP(launch_decode_combine(dl, stream));
+  }
+  return HEDDLE_OK;
+}
+
+int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+  {
+    const int rc_args = check_decode_args(ctx, args);
+    if (rc_args != HEDDLE_OK) return rc_args;
+  }
+  const int32_t B = args->B;
 
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;

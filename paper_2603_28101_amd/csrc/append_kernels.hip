@@ -25,6 +25,8 @@
 // for V.  Both are staged through LDS (coalesced 16-byte global loads into registers one step
 // ahead, XOR-swizzled K rows, double buffer, one barrier per 64 keys) and shared by the four
 // waves.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace heddle {
@@ -51,9 +53,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int G, int D>
-__global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
+// Launch = AppendLaunch: causal chunk rows of one trajectory, final bf16 output.
+// Launch = GroupLaunch: the decode queries of the trajectories of a group against a range of the
+// blocks they share (whole blocks, every key visible to every row), split-K partial output.
+template <int G, int D, typename Launch>
+__global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   static_assert(D == 128, "staging roles and swizzle are written for head_dim 128");
+  constexpr bool kGroup = std::is_same<Launch, GroupLaunch>::value;
   constexpr int NK = D / 16;             // MFMA steps over d for S^T
   constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
   constexpr int R = kTileRows / G;       // chunk rows per workgroup tile
@@ -76,23 +82,39 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
   const int n = lane & 31;               // query row (column of S^T / O^T) within the wave
   const int hi = lane >> 5;
 
-  const int b = a.tile_b[tile];
-  const int row0 = a.tile_row0[tile];
-  const int rows_n = a.tile_rows_n[tile];
-  const int extent = a.tile_extent[tile];          // keys visible to the tile's last row
-  const int L = a.ctx_len[b];
-  const int kv_len = L + (a.cu_chunk[b + 1] - a.cu_chunk[b]);
-  const int32_t* table = a.block_ids + a.row_off[b];
-
-  // this lane's query row
+  // this lane's query row: head g of the kv head's group, row r_in_tile of the tile
   const int n_global = wave * 32 + n;
   const int g = n_global / R;
   const int r_in_tile = n_global - g * R;
-  const bool row_valid = r_in_tile < rows_n;
-  const int chunk_row = row0 + min(r_in_tile, rows_n - 1);
-  const int64_t q_row = static_cast<int64_t>(a.cu_chunk[b]) + chunk_row;
-  const int pos = L + chunk_row;                   // last key this row may see
   const int head = h * G + g;
+
+  int rows_n, extent, kv_len, edge, pos, part = 0;
+  int64_t q_row;
+  const int32_t* table;
+  if constexpr (kGroup) {
+    const GroupItemRec rec = a.items[tile];
+    rows_n = rec.n_members;
+    extent = (rec.blk_end - rec.blk_begin) * kBlockTokens;   // keys are counted from the item's first block
+    kv_len = extent;
+    table = a.block_ids + rec.table_off + rec.blk_begin;
+    q_row = a.members[rec.member_off + min(r_in_tile, rows_n - 1)];
+    pos = extent - 1;
+    edge = extent - 1;
+    part = a.trajs[q_row].part_off + rec.part;
+  } else {
+    const int b = a.tile_b[tile];
+    const int row0 = a.tile_row0[tile];
+    rows_n = a.tile_rows_n[tile];
+    extent = a.tile_extent[tile];          // keys visible to the tile's last row
+    const int L = a.ctx_len[b];
+    kv_len = L + (a.cu_chunk[b + 1] - a.cu_chunk[b]);
+    table = a.block_ids + a.row_off[b];
+    const int chunk_row = row0 + min(r_in_tile, rows_n - 1);
+    q_row = static_cast<int64_t>(a.cu_chunk[b]) + chunk_row;
+    pos = L + chunk_row;                   // last key this row may see
+    edge = L + row0;                       // first position at which some row of the tile is masked
+  }
+  const bool row_valid = r_in_tile < rows_n;
 
   // Q^T operand: B[k = d][n = row], 8 consecutive d per lane and step
   bf16x8 qb[NK];
@@ -197,7 +219,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
     }
 
     // register j of tile u is key t0 + 32u + 8*(j/4) + 4*hi + j%4 of this lane's row
-    if (t0 + kChunkTokens - 1 > L + row0) {          // chunk reaches the causal edge of some row
+    if (t0 + kChunkTokens - 1 > edge) {              // chunk reaches the causal edge of some row
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -261,7 +283,21 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
 
   // ---- normalise and store: register j of tile mt is head-dim element mt*32 + 8*(j/4) + 4*hi + j%4
   l_sum += __shfl_xor(l_sum, 32, 64);
-  if (row_valid) {
+  if constexpr (kGroup) {
+    if (row_valid) {
+      const int64_t slot = static_cast<int64_t>(part) * a.n_q_heads + head;
+      float* ap = a.part_acc + slot * D;
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq)
+          *reinterpret_cast<float4*>(ap + mt * 32 + 8 * jq + 4 * hi) =
+              float4{o[mt][4 * jq + 0], o[mt][4 * jq + 1], o[mt][4 * jq + 2], o[mt][4 * jq + 3]};
+      // the weights enter P.V rounded and the sum does not; the combine kernel takes the same sum
+      // for the output's denominator and for the log-sum-exp of this part
+      if (hi == 0) *reinterpret_cast<float4*>(a.part_ml + slot * 4) = float4{m_ref, l_sum, l_sum, 0.0f};
+    }
+  } else if (row_valid) {
     const float inv = 1.0f / l_sum;
     uint16_t* op = a.out + (q_row * a.n_q_heads + head) * D;
 #pragma unroll
@@ -281,7 +317,14 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(AppendLaunch a) {
 template <int G, int D>
 hipError_t launch_append_t(const AppendLaunch& a, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(a.n_tiles) * static_cast<unsigned>(a.n_kv_heads));
-  hipLaunchKernelGGL((append_attn_kernel<G, D>), grid, dim3(256), 0, stream, a);
+  hipLaunchKernelGGL((append_attn_kernel<G, D, AppendLaunch>), grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <int G, int D>
+hipError_t launch_group_t(const GroupLaunch& a, hipStream_t stream) {
+  const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
+  hipLaunchKernelGGL((append_attn_kernel<G, D, GroupLaunch>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -301,6 +344,19 @@ hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream) {
     case 2: return launch_append_t<2, 128>(a, stream);
     case 4: return launch_append_t<4, 128>(a, stream);
     case 8: return launch_append_t<8, 128>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_group_attn(const GroupLaunch& a, hipStream_t stream) {
+  if (a.n_items <= 0) return hipSuccess;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  if (a.head_dim != 128) return hipErrorInvalidValue;
+  switch (G) {
+    case 1: return launch_group_t<1, 128>(a, stream);
+    case 2: return launch_group_t<2, 128>(a, stream);
+    case 4: return launch_group_t<4, 128>(a, stream);
+    case 8: return launch_group_t<8, 128>(a, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -37,6 +37,24 @@ struct DecodeItem {
 void plan_decode(const PlanParams& p, int32_t B, const int32_t* len, std::vector<DecodeItem>& items,
                  std::vector<int32_t>& nsplit, std::vector<int32_t>& part_off, int32_t& chunk);
 
+// Decode plan with shared prefixes: trajectories whose block-table rows start with the same
+// physical blocks form a group; the group's prefix is read once (group items, processed by the
+// matrix-core kernel for all members at a time), every member's remaining blocks are ordinary
+// decode items (rule in heddle.h).
+struct GroupItem {
+  int32_t g, k, blk_begin, blk_end, m0, mn;   // members[member_off[g] + m0 .. + mn)
+};
+struct SharedPlan {
+  int32_t chunk = 0, chunk_g = 0;
+  std::vector<int32_t> group_leader, group_prefix, group_parts, member_off, members;
+  std::vector<int32_t> traj_group, traj_prefix, nsplit, part_off;
+  std::vector<DecodeItem> items;     // s = slot within the trajectory (prefix parts come first)
+  std::vector<GroupItem> gitems;
+};
+void plan_decode_shared(const PlanParams& p, int32_t min_share_blk, int32_t group_wg_per_cu, int32_t tile_members,
+                        int32_t B, const int32_t* len, const int32_t* row_off, const int32_t* block_ids,
+                        SharedPlan& out);
+
 struct AppendTile {
   int32_t b, row0, rows, extent;
 };

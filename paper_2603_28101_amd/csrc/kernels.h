@@ -77,6 +77,35 @@ struct AppendLaunch {
   int32_t n_tiles, n_q_heads, n_kv_heads, head_dim;
   float scale_log2;
 };
+// One shared-prefix work item: the query rows of up to 128/G member trajectories of a group
+// against blocks [blk_begin, blk_end) of the prefix all of them share (32-byte record).
+struct GroupItemRec {
+  int32_t table_off;    // start of the group leader's row in block_ids
+  int32_t blk_begin;    // logical blocks of the shared prefix covered by this item
+  int32_t blk_end;
+  int32_t part;         // partial slot of this item within each member: trajs[b].part_off + part
+  int32_t member_off;   // members[member_off .. member_off + n_members) are the item's trajectories
+  int32_t n_members;
+  int32_t pad[2];
+};
+
+// Arguments of the shared-prefix pass of a decode step: same matrix-core kernel as append, no
+// causal edge, and the result is a split-K partial per (member, query head) that the combine
+// kernel merges with the partials of the member's private blocks.
+struct GroupLaunch {
+  const uint16_t* pool;
+  const int32_t* block_ids;
+  const GroupItemRec* items;   // [n_items] longest first
+  const int32_t* members;
+  const DecodeTrajRec* trajs;  // [B]
+  const uint16_t* q;           // bf16 [B][n_q][d]
+  float* part_acc;             // as in DecodeLaunch
+  float* part_ml;
+  int32_t n_items, n_q_heads, n_kv_heads, head_dim;
+  float scale_log2;
+};
+hipError_t launch_group_attn(const GroupLaunch& a, hipStream_t stream);
+
 bool append_shape_supported(int32_t group, int32_t head_dim);
 int32_t append_tile_rows(int32_t group);   // chunk rows per workgroup tile
 hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream);

@@ -190,3 +190,46 @@ def test_append_order_matches_oracle():
         c.plan_append([10], [0, 0], 32)          # empty chunk
     with pytest.raises(heddle.HeddleError):
         c.plan_append([-1], [0, 4], 32)
+
+
+# ------------------------------------------------------------------ shared-prefix decode plan
+
+def test_shared_plan_matches_oracle_on_random_tables():
+    from tests.test_oracle_planner import SHARED_KEYS, csr, random_shared_tables
+    rng = np.random.default_rng(123)
+    for trial in range(80):
+        B = int(rng.integers(1, 90))
+        lens, tables = random_shared_tables(rng, B, int(rng.integers(1, 4)), int(rng.choice([64, 400, 3000])))
+        row_off, ids = csr(tables)
+        G = int(rng.choice([1, 2, 4, 8]))
+        n_kv = int(rng.choice([1, 2, 8]))
+        prm = dict(n_cu=int(rng.choice([2, 16, 256])), wg_per_cu=int(rng.integers(1, 5)),
+                   min_chunk_blk=int(rng.choice([1, 4, 16])), tile_blk=int(rng.choice([1, 2, 4])),
+                   max_split=int(rng.choice([2, 8, 64])), min_share_blk=int(rng.choice([1, 2, 4])),
+                   group_wg_per_cu=int(rng.integers(1, 3)))
+        c = heddle.Context(n_kv * G, n_kv, 128, 4, **prm)
+        got = c.plan_decode_shared(lens, row_off, ids)
+        ref = op.plan_decode_shared(lens, row_off, ids, n_kv, 128 // G, **prm)
+        assert (got["chunk"], got["chunk_g"], got["n_groups"]) == (ref["chunk"], ref["chunk_g"], ref["n_groups"])
+        for k in SHARED_KEYS:
+            assert np.array_equal(got[k][: len(ref[k])], ref[k]), (trial, k)
+
+
+def test_shared_plan_on_unsupported_head_dim_forms_no_groups():
+    from tests.test_oracle_planner import csr
+    tables = [[1, 2, 3, 4, 5, 6, 10], [1, 2, 3, 4, 5, 6, 11]]
+    row_off, ids = csr(tables)
+    c = heddle.Context(8, 2, 64, 32)
+    plan = c.plan_decode_shared([100, 100], row_off, ids)
+    assert plan["n_groups"] == 0 and plan["n_gitems"] == 0
+    same_plan({**c.plan_decode([100, 100])}, {**plan, "n_items": plan["n_items"]})
+
+
+def test_shared_plan_errors():
+    from tests.test_oracle_planner import csr
+    row_off, ids = csr([[1, 2], [1, 3]])
+    c = host_ctx()
+    with pytest.raises(heddle.HeddleError):
+        c.plan_decode_shared([0, 20], row_off, ids)            # length < 1
+    with pytest.raises(heddle.HeddleError):
+        c.plan_decode_shared([40, 20], row_off, ids)           # table row too short

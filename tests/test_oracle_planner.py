@@ -174,3 +174,141 @@ def test_manager_conservation_random():
             assert got == [ids[-1]]
             held += got
         assert m.num_free() + len(held) == 50
+
+
+# ---------------------------------------------------------------- shared-prefix decode plan
+SHARED_KEYS = ("group_leader", "group_prefix", "group_parts", "member_off", "members", "traj_group",
+               "traj_prefix", "nsplit", "part_off", "item_b", "item_s", "item_blk_begin", "item_blk_end",
+               "gitem_g", "gitem_k", "gitem_blk_begin", "gitem_blk_end", "gitem_m0", "gitem_mn")
+
+
+def csr(tables):
+    row_off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int32)
+    ids = np.asarray([x for t in tables for x in t], dtype=np.int32)
+    return row_off, ids
+
+
+def test_shared_plan_hand_worked_examples():
+    for ex in load("shared_plan_worked_examples.json")["examples"]:
+        row_off, ids = csr(ex["tables"])
+        plan = op.plan_decode_shared(ex["lens"], row_off, ids, **ex["params"])
+        assert plan["chunk"] == ex["chunk"] and plan["chunk_g"] == ex["chunk_g"]
+        for k in SHARED_KEYS:
+            assert plan[k].tolist() == ex[k], k
+
+
+def check_shared_invariants(lens, row_off, ids, plan, tile_members, tile_blk, max_split, min_share_blk):
+    """What any valid shared plan must satisfy, whatever rule produced it."""
+    B = len(lens)
+    nblk = [-(-int(n) // 16) for n in lens]
+    covered = [np.zeros(n, dtype=np.int32) for n in nblk]
+    slots = [set() for _ in range(B)]
+    # private items
+    for b, s, lo, hi in zip(plan["item_b"], plan["item_s"], plan["item_blk_begin"], plan["item_blk_end"]):
+        assert plan["traj_prefix"][b] <= lo < hi <= nblk[b]
+        covered[b][lo:hi] += 1
+        assert s not in slots[b]
+        slots[b].add(int(s))
+    # group items: every member of the tile is covered through the leader's blocks, which it shares
+    for g, k, lo, hi, m0, mn in zip(plan["gitem_g"], plan["gitem_k"], plan["gitem_blk_begin"],
+                                    plan["gitem_blk_end"], plan["gitem_m0"], plan["gitem_mn"]):
+        p = int(plan["group_prefix"][g])
+        assert 0 <= lo < hi <= p and lo % tile_blk == 0 and 1 <= mn <= tile_members
+        mem = plan["members"][plan["member_off"][g]:plan["member_off"][g + 1]]
+        leader = int(plan["group_leader"][g])
+        assert mem[0] == leader and list(mem) == sorted(mem)
+        for b in mem[m0:m0 + mn]:
+            assert plan["traj_group"][b] == g and plan["traj_prefix"][b] == p
+            assert p >= min_share_blk and p * 16 <= int(lens[b]) - 1      # never the block of the step's own row
+            assert np.array_equal(ids[row_off[b]:row_off[b] + p], ids[row_off[leader]:row_off[leader] + p])
+            covered[b][lo:hi] += 1
+            slots[b].add(int(k))
+    for b in range(B):
+        assert (covered[b] == 1).all(), f"trajectory {b}: every block exactly once"
+        assert slots[b] == set(range(int(plan["nsplit"][b])))
+        assert plan["part_off"][b + 1] - plan["part_off"][b] == plan["nsplit"][b]
+        if plan["traj_group"][b] < 0:
+            assert plan["traj_prefix"][b] == 0
+    for g in range(plan["n_groups"]):
+        assert plan["group_parts"][g] <= max_split
+        assert plan["member_off"][g + 1] - plan["member_off"][g] >= 2
+    d = plan["item_blk_end"] - plan["item_blk_begin"]
+    assert (np.diff(d) <= 0).all()
+    dg = plan["gitem_blk_end"] - plan["gitem_blk_begin"]
+    assert (np.diff(dg) <= 0).all()
+
+
+def random_shared_tables(rng, B, n_groups, max_len):
+    """Block tables in which random subsets of trajectories share random numbers of leading
+    blocks (sometimes diverging early, sometimes sharing only the first id)."""
+    lens = rng.integers(1, max_len, B)
+    nblk = -(-lens // 16)
+    next_id = [1000]
+
+    def fresh(n):
+        out = list(range(next_id[0], next_id[0] + n))
+        next_id[0] += n
+        return out
+
+    prompts = [fresh(int(rng.integers(1, max_len // 16 + 2))) for _ in range(n_groups)]
+    tables = []
+    for b in range(B):
+        g = int(rng.integers(-1, n_groups))
+        if g < 0:
+            tables.append(fresh(int(nblk[b])))
+            continue
+        share = int(rng.integers(1, len(prompts[g]) + 1))
+        share = min(share, (int(lens[b]) - 1) // 16 + int(rng.integers(0, 2)), int(nblk[b]))   # sometimes one too many
+        tables.append(prompts[g][:share] + fresh(int(nblk[b]) - share))
+    return lens.astype(np.int32), tables
+
+
+def test_shared_plan_invariants_random():
+    rng = np.random.default_rng(77)
+    for trial in range(60):
+        B = int(rng.integers(1, 40))
+        lens, tables = random_shared_tables(rng, B, int(rng.integers(1, 5)), int(rng.choice([64, 400, 3000])))
+        row_off, ids = csr(tables)
+        prm = dict(n_kv_heads=int(rng.choice([1, 2, 8])), tile_members=int(rng.choice([2, 16, 32])),
+                   n_cu=int(rng.choice([2, 16, 256])), wg_per_cu=int(rng.integers(1, 5)),
+                   min_chunk_blk=int(rng.choice([1, 4, 16])), tile_blk=int(rng.choice([1, 2, 4])),
+                   max_split=int(rng.choice([2, 8, 64])), min_share_blk=int(rng.choice([1, 2, 4])),
+                   group_wg_per_cu=int(rng.integers(1, 3)))
+        plan = op.plan_decode_shared(lens, row_off, ids, **prm)
+        check_shared_invariants(lens, row_off, ids, plan, prm["tile_members"], prm["tile_blk"], prm["max_split"],
+                                prm["min_share_blk"])
+
+
+def test_shared_plan_without_sharing_is_the_plain_plan():
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, 9000, 30).astype(np.int32)
+    tables = []
+    nxt = 0
+    for n in lens:
+        k = -(-int(n) // 16)
+        tables.append(list(range(nxt, nxt + k)))
+        nxt += k
+    row_off, ids = csr(tables)
+    a = op.plan_decode(lens, 8)
+    b = op.plan_decode_shared(lens, row_off, ids, 8, 32)
+    assert b["n_groups"] == 0 and b["n_gitems"] == 0 and a["chunk"] == b["chunk"]
+    for k in ("item_b", "item_s", "item_blk_begin", "item_blk_end", "nsplit", "part_off"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_shared_plan_named_workload():
+    """Workload 6: the 8 prompts are found with exactly their whole shared blocks, 16 members each."""
+    lens, group_of, prompt = hw.draw_group_lengths(np.random.default_rng([6, 0]))
+    # tables with sharing, built here from the definition (ids need not be permuted for the plan)
+    tables, nxt = [], 10_000
+    for b in range(len(lens)):
+        p = int(prompt[group_of[b]]) // 16
+        n = -(-int(lens[b]) // 16)
+        tables.append([int(group_of[b]) * 1000 + i for i in range(p)] + list(range(nxt, nxt + n - p)))
+        nxt += n - p
+    row_off, ids = csr(tables)
+    plan = op.plan_decode_shared(lens, row_off, ids, 8, 32)
+    assert plan["n_groups"] == 8
+    assert sorted(plan["group_prefix"].tolist()) == sorted((prompt // 16).tolist())
+    assert (np.diff(plan["member_off"]) == 16).all()
+    check_shared_invariants(lens, row_off, ids, plan, 32, 4, 64, 4)
