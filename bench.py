@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--op", default="attention", choices=["attention", "pack"],
                     help="attention: the workload's decode or append pass (default); pack: gather of every "
                          "trajectory's blocks into one contiguous staging buffer (whole-block copy)")
@@ -72,6 +72,7 @@ def main():
     stream = torch.cuda.Stream()
 
     kind = "pack" if args.op == "pack" else w.kind
+    shared = False
     if kind == "pack":
         used = np.concatenate([case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]]
                                for b in range(w.B)]).astype(np.int32)
@@ -86,9 +87,21 @@ def main():
     elif kind == "decode":
         lens = case["lens"]
         unit_bytes = hw.kv_bytes(lens, w.n_kv_heads, w.head_dim)   # algorithmic bytes of one step
+        shared = "group_of" in case
+        if shared:
+            # blocks that several trajectories name are read once: bytes of the distinct tokens
+            logical_bytes = unit_bytes
+            unit_bytes = hw.kv_bytes([hw.unique_kv_tokens(case)], w.n_kv_heads, w.head_dim)
+            plan = ctx.plan_decode_shared(lens, case["row_off"], case["block_ids"])
+            private_tokens = int(lens.astype(np.int64).sum() - 16 * plan["traj_prefix"].astype(np.int64).sum())
+            private_bytes = hw.kv_bytes([private_tokens], w.n_kv_heads, w.head_dim)
 
-        def step():
-            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+            def step():
+                ctx.attn_decode_shared(lens, case["row_off"], case["block_ids"], row_off, block_ids, q, out, None,
+                                       stream=stream)
+        else:
+            def step():
+                ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
 
         dominant, bound = 0, "hbm"
     else:
@@ -124,6 +137,7 @@ def main():
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     aux_us = ctx.timing_read({"decode": 1, "append": 3, "pack": 5}[kind])[0]
+    group_us = ctx.timing_read(6)[0] if shared else 0.0
     ctx.timing_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -137,11 +151,15 @@ def main():
     elif kind == "decode":
         value = unit_bytes / (ms_per_step * 1e-3) / 1e9
         metric, unit = "decode-attention KV GB/s", "GB/s"
-        achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
+        # the split-K kernel reads every block exactly one trajectory names (all blocks without sharing)
+        achieved = (private_bytes if shared else unit_bytes) / (kernel_us * 1e-6) / 1e9
         roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                     "kernel": "decode_splitk_kernel", "kernel_avg_us": round(kernel_us, 2),
                     "launches_timed": n_launch, "combine_avg_us": round(aux_us, 2)}
+        if shared:
+            roofline["kernel_bytes"] = private_bytes
+            roofline["shared_prefix_kernel_avg_us"] = round(group_us, 2)
     else:
         value = unit_flops / (ms_per_step * 1e-3) / 1e12
         metric, unit = "append-attention TFLOP/s", "TFLOP/s"
@@ -174,6 +192,22 @@ def main():
 
     roofline["traffic"] = recorded_traffic(w, roofline["kernel"])
 
+    extra = {}
+    if kind == "decode" and shared:
+        # the same batch through the plain decode entry point, which reads a shared block once per
+        # trajectory that names it
+        for _ in range(5):
+            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(20):
+            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+        torch.cuda.synchronize()
+        plain_us = (time.perf_counter() - t2) * 1e6 / 20
+        extra = {"kv_bytes_if_every_trajectory_read_its_own": logical_bytes,
+                 "plain_decode_us_per_step": round(plain_us, 1),
+                 "speedup_over_plain_decode": round(plain_us / (ms_per_step * 1e3), 3)}
+
     result = {
         "metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -187,6 +221,7 @@ def main():
         "frac_of_hbm_peak_whole_step": round(unit_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "stream_read_ceiling_GBps": round(stream_gbps, 1),
         "roofline": roofline,
+        **extra,
     }
 
     if not args.no_cpu_baseline:

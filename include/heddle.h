@@ -78,7 +78,7 @@ typedef struct heddle_config {
   float   scale;          /* 0 selects 1/sqrt(head_dim) */
   /* shared-prefix planner parameters (heddle_plan_decode_shared); 0 selects the default */
   int32_t min_share_blk;    /* [4] fewest common leading blocks that make two trajectories a group */
-  int32_t group_wg_per_cu;  /* [2] work items wanted per CU for the shared-prefix kernel */
+  int32_t group_wg_per_cu;  /* [1] work items wanted per CU for the shared-prefix kernel */
 } heddle_config;
 
 /* Creates a context.  *out is written only on success.  With device >= 0 the

@@ -94,7 +94,7 @@ def plan_append(ctx_lens, chunk_lens, tile_rows: int):
 
 def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: int, n_cu=256,
                        wg_per_cu=4, min_chunk_blk=16, tile_blk=4, max_split=64, min_share_blk=4,
-                       group_wg_per_cu=2):
+                       group_wg_per_cu=1):
     """Split-K plan for a decode step in which trajectories whose block-table rows begin with
     the same physical blocks (the samples of one prompt, Sec. 7 Workloads; a prefix-cache hit
     in the sense of Sec. 2.3) read that shared prefix once per group instead of once each.

@@ -59,7 +59,7 @@ struct heddle_ctx {
   std::vector<int32_t> nsplit, part_off;
   std::vector<AppendTile> tiles;
   SharedPlan shared;
-  int32_t min_share_blk = 4, group_wg_per_cu = 2;
+  int32_t min_share_blk = 4, group_wg_per_cu = 1;
 };
 
 namespace {
@@ -212,7 +212,7 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   ctx->plan.tile_blk = cfg->tile_blk ? cfg->tile_blk : 4;
   ctx->plan.max_split = cfg->max_split ? cfg->max_split : 64;
   ctx->min_share_blk = cfg->min_share_blk ? cfg->min_share_blk : 4;
-  ctx->group_wg_per_cu = cfg->group_wg_per_cu ? cfg->group_wg_per_cu : 2;
+  ctx->group_wg_per_cu = cfg->group_wg_per_cu ? cfg->group_wg_per_cu : 1;
   *out = ctx.release();
   return HEDDLE_OK;
 }
