@@ -251,6 +251,42 @@ int heddle_kv_pack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, vo
 int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, const void* staging,
                      void* hip_stream);
 
+/* ---- trajectory placement (host only, no context) -----------------------------
+ * Presorted dynamic programming of Sec. 5.2: n trajectories in DESCENDING length
+ * order are split into at most m contiguous runs, one per worker, minimising
+ *   max over workers of  (L_first * T) * F[size]          (Eq. 2 under Lemma 1)
+ * with dp[i][1] = L_1 T F(i), dp[i][j] = min_k max(dp[k][j-1], L_{k+1} T F(i-k))   (Eq. 3).
+ * F is a table over group sizes 0 .. F_len-1 and must reach the total member count.
+ * count (or NULL = all ones) gives members per element, for bundled short
+ * trajectories; a group's size is the sum of its elements' counts.  min(n, m) workers
+ * get a non-empty run, the rest size 0; among equal optima the smallest split index k
+ * wins at every step.  sizes_out [m] = elements per worker, longest trajectories first.
+ * mode 0: when F is non-decreasing the minimum over k is found at the crossing of
+ * the two monotone terms (O(n m log n)), else by the full scan; mode 1: always the
+ * full scan of Eq. 3 (O(n^2 m)).  Both give the same result bit for bit.
+ * Errors: lengths not descending, count < 1, F too short, m < 1, NULL -> INVAL. */
+int heddle_placement_dp(int32_t n, const double* len_desc, const int32_t* count, int32_t m, const double* F,
+                        int32_t F_len, double T, int32_t mode, int32_t* sizes_out, double* makespan_out);
+
+/* Bundles the short tail of the sorted list (Sec. 5.2: trajectories under a threshold
+ * are merged after the sort to shrink n): an element is one trajectory of length >=
+ * threshold, or up to `bundle` consecutive shorter ones.  first_out / count_out [n]. */
+int heddle_placement_aggregate(int32_t n, const double* len_desc, double threshold, int32_t bundle,
+                               int32_t* first_out, int32_t* count_out, int32_t* n_elems_out);
+
+/* Interference factor from a profile (Sec. 5.2, "Interference Factor"): step_time[i] is
+ * the time of one decode step at batch size batch_sizes[i] (strictly increasing).
+ * t(s) interpolates linearly (flat below the first point, last slope continued);
+ * F_out[s] = t(s) / t(1) for s = 1..n under a running maximum, F_out[0] = 0. */
+int heddle_interference_table(int32_t n_prof, const double* batch_sizes, const double* step_time, int32_t n,
+                              double* F_out /* [n+1] */);
+
+/* Simulator of one worker's group: all trajectories decode concurrently, a step with
+ * a of them active takes t(a), a trajectory of length L leaves after L steps.
+ * *time_out = total time in the profile's unit. */
+int heddle_simulate_group(int32_t n, const int32_t* lengths, int32_t n_prof, const double* batch_sizes,
+                          const double* step_time, double* time_out);
+
 /* ---- measurement aids ---------------------------------------------------------
  * Average duration in microseconds of the dominant kernel of the last
  * `heddle_attn_decode` / `heddle_attn_append` calls, measured with HIP events

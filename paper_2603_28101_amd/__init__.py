@@ -10,6 +10,10 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     stream_read,
+    placement_dp,
+    placement_aggregate,
+    interference_table,
+    simulate_group,
     E_INVAL,
     E_NOMEM,
     E_HIP,

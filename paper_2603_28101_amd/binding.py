@@ -107,6 +107,12 @@ lib.heddle_attn_decode_shared.argtypes = [vp, C.POINTER(DecodeArgs), i32p, vp]
 lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
 lib.heddle_kv_pack.argtypes = [vp, C.c_int32, i32p, vp, vp]
 lib.heddle_kv_unpack.argtypes = [vp, C.c_int32, i32p, vp, vp]
+f64p = C.POINTER(C.c_double)
+lib.heddle_placement_dp.argtypes = [C.c_int32, f64p, i32p, C.c_int32, f64p, C.c_int32, C.c_double, C.c_int32,
+                                    i32p, f64p]
+lib.heddle_placement_aggregate.argtypes = [C.c_int32, f64p, C.c_double, C.c_int32, i32p, i32p, i32p]
+lib.heddle_interference_table.argtypes = [C.c_int32, f64p, f64p, C.c_int32, f64p]
+lib.heddle_simulate_group.argtypes = [C.c_int32, i32p, C.c_int32, f64p, f64p, f64p]
 lib.heddle_timing_enable.argtypes = [vp, C.c_int32]
 lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
@@ -116,7 +122,8 @@ lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
-           "heddle_timing_read", "heddle_stream_read",
+           "heddle_timing_read", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
+           "heddle_interference_table", "heddle_simulate_group",
            "heddle_version"):
     getattr(lib, _f).restype = C.c_int
 
@@ -156,6 +163,55 @@ def _stream_ptr(stream):
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(f64p)
+
+
+def placement_dp(lengths_desc, m, F, T=1.0, counts=None, full_scan=False):
+    """(makespan, sizes[m]) of the presorted dynamic programming over descending lengths."""
+    L, Lp = _f64(lengths_desc)
+    Ft, Fp = _f64(F)
+    cp = None
+    if counts is not None:
+        cnt, cp = _i32(counts)
+    sizes = np.zeros(max(int(m), 1), dtype=np.int32)
+    mk = C.c_double()
+    _check(lib.heddle_placement_dp(L.shape[0], Lp, cp, int(m), Fp, Ft.shape[0], float(T), 1 if full_scan else 0,
+                                   sizes.ctypes.data_as(i32p), C.byref(mk)), "heddle_placement_dp")
+    return mk.value, sizes
+
+
+def placement_aggregate(lengths_desc, threshold, bundle):
+    L, Lp = _f64(lengths_desc)
+    first = np.empty(max(L.shape[0], 1), dtype=np.int32)
+    count = np.empty(max(L.shape[0], 1), dtype=np.int32)
+    n = C.c_int32()
+    _check(lib.heddle_placement_aggregate(L.shape[0], Lp, float(threshold), int(bundle), first.ctypes.data_as(i32p),
+                                          count.ctypes.data_as(i32p), C.byref(n)), "heddle_placement_aggregate")
+    return first[: n.value].copy(), count[: n.value].copy()
+
+
+def interference_table(batch_sizes, step_time, n):
+    bs, bsp = _f64(batch_sizes)
+    ts, tsp = _f64(step_time)
+    if bs.shape != ts.shape:
+        raise ValueError("one step time per batch size")
+    F = np.empty(int(n) + 1, dtype=np.float64)
+    _check(lib.heddle_interference_table(bs.shape[0], bsp, tsp, int(n), F.ctypes.data_as(f64p)),
+           "heddle_interference_table")
+    return F
+
+
+def simulate_group(lengths, batch_sizes, step_time):
+    L, Lp = _i32(lengths)
+    bs, bsp = _f64(batch_sizes)
+    ts, tsp = _f64(step_time)
+    out = C.c_double()
+    _check(lib.heddle_simulate_group(L.shape[0], Lp, bs.shape[0], bsp, tsp, C.byref(out)), "heddle_simulate_group")
+    return out.value
 
 
 class Context:

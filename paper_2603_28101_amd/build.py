@@ -15,6 +15,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = [
     "host_manager.cpp",
     "host_planner.cpp",
+    "host_placement.cpp",
     "api.hip",
     "decode_kernels.hip",
     "append_kernels.hip",

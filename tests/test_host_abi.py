@@ -233,3 +233,70 @@ def test_shared_plan_errors():
         c.plan_decode_shared([0, 20], row_off, ids)            # length < 1
     with pytest.raises(heddle.HeddleError):
         c.plan_decode_shared([40, 20], row_off, ids)           # table row too short
+
+
+# ------------------------------------------------------------------ placement (Sec. 5.2)
+
+def test_placement_golden_examples_on_library():
+    for ex in json.load(open(os.path.join(GOLDEN, "placement_worked_examples.json")))["examples"]:
+        for full_scan in (False, True):
+            mk, sizes = heddle.placement_dp(ex["lengths"], ex["m"], ex["F"], ex["T"], full_scan=full_scan)
+            assert mk == ex["makespan"] and sizes.tolist() == ex["sizes"]
+
+
+def test_placement_matches_oracle_bit_for_bit():
+    from oracle import placement as pl
+    rng = np.random.default_rng(11)
+    for trial in range(120):
+        n, m = int(rng.integers(0, 60)), int(rng.integers(1, 12))
+        kind = trial % 4
+        if kind == 0:       # many ties: few distinct lengths, flat stretches in F
+            L = sorted(rng.choice([5, 9, 9, 30], n).tolist(), reverse=True)
+            F = np.concatenate([[0.0], 1.0 + np.cumsum(rng.choice([0.0, 0.0, 0.5], max(n, 1)))])
+        elif kind == 1:     # long tail, smooth F
+            L = sorted(rng.lognormal(7, 1.2, n).tolist(), reverse=True)
+            F = np.concatenate([[0.0], 1.0 + np.cumsum(rng.uniform(0, 0.3, max(n, 1)))])
+        elif kind == 2:     # F that is not monotone: the library must fall back to the full scan
+            L = sorted(rng.integers(1, 500, n).tolist(), reverse=True)
+            F = np.concatenate([[0.0], rng.uniform(0.5, 3.0, max(n, 1))])
+        else:               # bundled elements
+            L = sorted(rng.integers(1, 500, n).tolist(), reverse=True)
+            F = np.concatenate([[0.0], 1.0 + np.cumsum(rng.uniform(0, 0.3, 4 * max(n, 1)))])
+        counts = rng.integers(1, 5, n).tolist() if kind == 3 else None
+        T = float(rng.uniform(0.1, 3.0))
+        ref_mk, ref_sizes = pl.placement_dp(L, m, F.tolist(), T, counts)
+        for full_scan in (False, True):
+            mk, sizes = heddle.placement_dp(L, m, F, T, counts, full_scan=full_scan)
+            assert mk == ref_mk and sizes.tolist() == ref_sizes, (trial, full_scan)
+
+
+def test_placement_helpers_match_oracle():
+    from oracle import placement as pl
+    rng = np.random.default_rng(12)
+    for trial in range(40):
+        n = int(rng.integers(0, 40))
+        L = sorted(rng.integers(1, 100, n).tolist(), reverse=True)
+        thr, bundle = int(rng.integers(0, 100)), int(rng.integers(0, 6))
+        f, c = heddle.placement_aggregate(L, thr, bundle)
+        rf, rc = pl.aggregate_short(L, thr, bundle)
+        assert f.tolist() == rf and c.tolist() == rc
+        k = int(rng.integers(1, 6))
+        bs = np.cumsum(rng.integers(1, 9, k)).astype(float)
+        ts = rng.uniform(1.0, 50.0, k)
+        assert heddle.interference_table(bs, ts, 70).tolist() == pl.interference_table(bs, ts, 70)
+        lens = rng.integers(0, 300, n)
+        assert heddle.simulate_group(lens, bs, ts) == pl.simulate_group(lens, bs, ts)
+
+
+def test_placement_errors():
+    F = [0.0, 1.0, 2.0, 3.0]
+    with pytest.raises(heddle.HeddleError):
+        heddle.placement_dp([1, 2, 3], 2, F)                 # ascending
+    with pytest.raises(heddle.HeddleError):
+        heddle.placement_dp([3, 2, 1], 0, F)                 # no worker
+    with pytest.raises(heddle.HeddleError):
+        heddle.placement_dp([3, 2, 1], 2, F[:3])             # F does not reach size 3
+    with pytest.raises(heddle.HeddleError):
+        heddle.placement_dp([3, 2, 1], 2, F, counts=[1, 0, 1])
+    with pytest.raises(heddle.HeddleError):
+        heddle.interference_table([2, 2], [1.0, 2.0], 4)
