@@ -79,6 +79,9 @@ typedef struct heddle_config {
   /* shared-prefix planner parameters (heddle_plan_decode_shared); 0 selects the default */
   int32_t min_share_blk;    /* [4] fewest common leading blocks that make two trajectories a group */
   int32_t group_wg_per_cu;  /* [1] work items wanted per CU for the shared-prefix kernel */
+  /* split-K of small append batches (heddle_plan_append_split); 0 selects the default */
+  int32_t append_wg_per_cu; /* [2] workgroups of the append kernel that fit on a CU */
+  int32_t append_min_steps; /* [4] smallest part, in 64-key steps */
 } heddle_config;
 
 /* Creates a context.  *out is written only on success.  With device >= 0 the
@@ -140,6 +143,33 @@ typedef struct heddle_append_plan {
 } heddle_append_plan;
 int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
                        const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_plan* plan);
+
+/* ---- split-K of a small append batch (host only) ------------------------------
+ * An append batch with few tiles (one long trajectory with a short chunk; the
+ * verify step of speculative decoding, a few tokens per trajectory, Sec. 8) would
+ * leave most of the GPU idle; the keys of its tiles are then cut into parts that
+ * run as separate work items and are merged per row afterwards.  Rule (integer),
+ * tiles as produced by heddle_plan_append, index t in that order:
+ *  1. S_t = ceil(extent_t / 64); slots = n_cu * append_wg_per_cu; if
+ *     n_tiles * n_kv_heads >= slots nothing is split.
+ *  2. else W = sum S_t, target = max(1, slots / n_kv_heads), chunk = max(ceil(W /
+ *     target), append_min_steps); per tile ns = min(ceil(S/chunk), max_split), per =
+ *     ceil(S/ns), n = ceil(S/per); if n > 1 and (n-1)*per*64 > L_b + row0 then n -= 1
+ *     (the tile's first row must see a key of the last part).  Part k < n-1 covers
+ *     steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
+ *  3. a tile with n > 1 owns rows_n * n partial slots from part_base_t (assigned in
+ *     tile order); row r, part k -> part_base_t + r*n + k.
+ *  4. items (t, k) sorted by (-(step_end - step_begin), t, k).
+ * heddle_attn_append applies this rule itself; the function exposes it for checking. */
+typedef struct heddle_append_split_plan {
+  int32_t  cap_tiles, cap_items;            /* in  */
+  int32_t  n_tiles, n_items, n_slots, tile_rows;   /* out */
+  int32_t* tile_b; int32_t* tile_row0; int32_t* tile_rows_n; int32_t* tile_extent;   /* [n_tiles] */
+  int32_t* tile_nsplit; int32_t* tile_part_base;                                     /* [n_tiles] */
+  int32_t* item_tile; int32_t* item_k; int32_t* item_step_begin; int32_t* item_step_end;   /* [n_items] */
+} heddle_append_split_plan;
+int heddle_plan_append_split(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
+                             const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_split_plan* plan);
 
 /* ---- decode: one query token per trajectory ---------------------------------
  * len[b] counts the KV rows the query sees, the new token's own row included.

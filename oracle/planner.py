@@ -224,3 +224,59 @@ def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: 
         nsplit=i32(nsplit),
         part_off=i32(part_off),
     )
+
+
+APPEND_STEP_KEYS = 64     # keys per main-loop step of the append kernel; parts are cut at these
+
+
+def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_cu=2, min_steps=4,
+                       max_split=64):
+    """Split-K for an append batch too small to fill the GPU (one long trajectory with a short
+    chunk; a speculative-decoding verify step of a few tokens per trajectory, Sec. 8): the keys
+    of a tile are cut into parts that run as separate work items and are merged afterwards.
+
+    Rule (integer; `plan` is the output of plan_append, tiles in its order, index t):
+      1. S_t = ceil(extent_t / 64) steps.  slots = n_cu * append_wg_per_cu.  If
+         n_tiles * n_kv_heads >= slots nothing is split (nsplit_t = 1 for all t).
+      2. Otherwise W = sum S_t, target = max(1, slots // n_kv_heads),
+         chunk = max(ceil(W / target), min_steps).  Per tile ns = min(ceil(S/chunk), max_split),
+         per = ceil(S / ns), n = ceil(S / per); if n > 1 and (n-1) * per * 64 > L_b + row0 then
+         n -= 1 (the first row of the tile must see a key of the last part).  Part k < n-1
+         covers steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
+      3. Tiles with n > 1 own rows_n * n partial slots from part_base_t on (bases assigned in
+         tile order); row r of the tile, part k -> slot part_base_t + r*n + k.
+      4. items (t, k) sorted by (-(step_end - step_begin), t, k).
+    Returns tile_nsplit[n_tiles], tile_part_base[n_tiles], n_slots, and item arrays
+    item_tile, item_k, item_step_begin, item_step_end."""
+    n_tiles = int(plan["n_tiles"])
+    S = [_ceil_div(int(e), APPEND_STEP_KEYS) for e in plan["tile_extent"]]
+    slots = n_cu * append_wg_per_cu
+    nsplit, per_of = [1] * n_tiles, list(S)
+    if n_tiles * n_kv_heads < slots:
+        W = sum(S)
+        target = max(1, slots // n_kv_heads)
+        chunk = max(_ceil_div(W, target), min_steps)
+        for t in range(n_tiles):
+            ns = min(_ceil_div(S[t], chunk), max_split)
+            per = _ceil_div(S[t], ns)
+            n = _ceil_div(S[t], per)
+            first_row_pos = int(ctx_lens[int(plan["tile_b"][t])]) + int(plan["tile_row0"][t])
+            if n > 1 and (n - 1) * per * APPEND_STEP_KEYS > first_row_pos:
+                n -= 1
+            nsplit[t], per_of[t] = n, per
+    base, part_base, items = 0, [], []
+    for t in range(n_tiles):
+        part_base.append(base if nsplit[t] > 1 else 0)
+        if nsplit[t] > 1:
+            base += int(plan["tile_rows_n"][t]) * nsplit[t]
+        for k in range(nsplit[t]):
+            lo = k * per_of[t]
+            hi = S[t] if k == nsplit[t] - 1 else (k + 1) * per_of[t]
+            items.append((-(hi - lo), t, k, lo, hi))
+    items.sort()
+    i32 = lambda v: np.asarray(v, dtype=np.int32)
+    return dict(
+        tile_nsplit=i32(nsplit), tile_part_base=i32(part_base), n_slots=base, n_items=len(items),
+        item_tile=i32([it[1] for it in items]), item_k=i32([it[2] for it in items]),
+        item_step_begin=i32([it[3] for it in items]), item_step_end=i32([it[4] for it in items]),
+    )

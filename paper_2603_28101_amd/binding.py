@@ -43,6 +43,7 @@ class Config(C.Structure):
         ("tile_blk", C.c_int32), ("max_split", C.c_int32),
         ("scale", C.c_float),
         ("min_share_blk", C.c_int32), ("group_wg_per_cu", C.c_int32),
+        ("append_wg_per_cu", C.c_int32), ("append_min_steps", C.c_int32),
     ]
 
 
@@ -67,6 +68,15 @@ class SharedPlan(C.Structure):
         + [(k, i32p) for k in _SHARED_ITEM + _SHARED_GITEM + _SHARED_GROUP]
         + [("member_off", i32p)] + [(k, i32p) for k in _SHARED_TRAJ] + [("part_off", i32p)]
     )
+
+
+_SPLIT_TILE = ("tile_b", "tile_row0", "tile_rows_n", "tile_extent", "tile_nsplit", "tile_part_base")
+_SPLIT_ITEM = ("item_tile", "item_k", "item_step_begin", "item_step_end")
+
+
+class AppendSplitPlan(C.Structure):
+    _fields_ = ([(k, C.c_int32) for k in ("cap_tiles", "cap_items", "n_tiles", "n_items", "n_slots", "tile_rows")]
+                + [(k, i32p) for k in _SPLIT_TILE + _SPLIT_ITEM])
 
 
 class AppendPlan(C.Structure):
@@ -102,6 +112,7 @@ lib.heddle_kv_num_free.argtypes = [vp, i32p]
 lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
 lib.heddle_attn_decode.argtypes = [vp, C.POINTER(DecodeArgs), vp]
+lib.heddle_plan_append_split.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendSplitPlan)]
 lib.heddle_plan_decode_shared.argtypes = [vp, C.c_int32, i32p, i32p, i32p, C.POINTER(SharedPlan)]
 lib.heddle_attn_decode_shared.argtypes = [vp, C.POINTER(DecodeArgs), i32p, vp]
 lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
@@ -121,7 +132,7 @@ lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
-           "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
+           "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
            "heddle_timing_read", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
            "heddle_interference_table", "heddle_simulate_group",
            "heddle_version"):
@@ -219,10 +230,10 @@ class Context:
 
     def __init__(self, n_q_heads, n_kv_heads, head_dim, n_blocks, kv_pool=None, device=-1, *,
                  n_cu=0, wg_per_cu=0, min_chunk_blk=0, tile_blk=0, max_split=0, scale=0.0,
-                 min_share_blk=0, group_wg_per_cu=0):
+                 min_share_blk=0, group_wg_per_cu=0, append_wg_per_cu=0, append_min_steps=0):
         self.cfg = Config(n_q_heads, n_kv_heads, head_dim, 16, n_blocks, device, _dptr(kv_pool),
                           n_cu, wg_per_cu, min_chunk_blk, tile_blk, max_split, scale,
-                          min_share_blk, group_wg_per_cu)
+                          min_share_blk, group_wg_per_cu, append_wg_per_cu, append_min_steps)
         self._pool = kv_pool  # keep the tensor alive
         self._h = vp()
         _check(lib.heddle_ctx_create(C.byref(self.cfg), C.byref(self._h)), "heddle_ctx_create")
@@ -311,6 +322,22 @@ class Context:
         _check(lib.heddle_plan_append(self._h, B, Lp, cup, tile_rows, C.byref(p)), "heddle_plan_append")
         out = {k: v[: p.n_tiles].copy() for k, v in arrs.items()}
         out.update(n_tiles=p.n_tiles, tile_rows=p.tile_rows)
+        return out
+
+    def plan_append_split(self, ctx_lens, cu_chunk, tile_rows: int = 0) -> dict:
+        L, Lp = _i32(ctx_lens)
+        cu, cup = _i32(cu_chunk)
+        B = L.shape[0]
+        cap_tiles = max(int(cu[-1]), 1)
+        cap_items = cap_tiles * self.max_split
+        arrs = {k: np.empty(cap_tiles, dtype=np.int32) for k in _SPLIT_TILE}
+        arrs.update({k: np.empty(cap_items, dtype=np.int32) for k in _SPLIT_ITEM})
+        p = AppendSplitPlan(cap_tiles, cap_items, 0, 0, 0, 0,
+                            *(arrs[k].ctypes.data_as(i32p) for k in _SPLIT_TILE + _SPLIT_ITEM))
+        _check(lib.heddle_plan_append_split(self._h, B, Lp, cup, tile_rows, C.byref(p)), "heddle_plan_append_split")
+        out = {k: arrs[k][: p.n_tiles].copy() for k in _SPLIT_TILE}
+        out.update({k: arrs[k][: p.n_items].copy() for k in _SPLIT_ITEM})
+        out.update(n_tiles=p.n_tiles, n_items=p.n_items, n_slots=p.n_slots, tile_rows=p.tile_rows)
         return out
 
     # ---- attention

@@ -60,6 +60,8 @@ struct heddle_ctx {
   std::vector<AppendTile> tiles;
   SharedPlan shared;
   int32_t min_share_blk = 4, group_wg_per_cu = 1;
+  AppendSplit split;
+  int32_t append_wg_per_cu = 2, append_min_steps = 4;
 };
 
 namespace {
@@ -178,7 +180,7 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   if (cfg->block_tokens != HEDDLE_BLOCK_TOKENS || cfg->n_blocks < 1) return HEDDLE_E_INVAL;
   if (cfg->head_dim < 8 || cfg->head_dim % 8 != 0) return HEDDLE_E_INVAL;
   if (cfg->n_cu < 0 || cfg->wg_per_cu < 0 || cfg->min_chunk_blk < 0 || cfg->tile_blk < 0 || cfg->max_split < 0 ||
-      cfg->min_share_blk < 0 || cfg->group_wg_per_cu < 0)
+      cfg->min_share_blk < 0 || cfg->group_wg_per_cu < 0 || cfg->append_wg_per_cu < 0 || cfg->append_min_steps < 0)
     return HEDDLE_E_INVAL;
   if (cfg->device < -1 || (cfg->device >= 0 && cfg->kv_pool == nullptr)) return HEDDLE_E_INVAL;
   if (!(cfg->scale >= 0.f) || !std::isfinite(cfg->scale)) return HEDDLE_E_INVAL;
@@ -213,6 +215,8 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   ctx->plan.max_split = cfg->max_split ? cfg->max_split : 64;
   ctx->min_share_blk = cfg->min_share_blk ? cfg->min_share_blk : 4;
   ctx->group_wg_per_cu = cfg->group_wg_per_cu ? cfg->group_wg_per_cu : 1;
+  ctx->append_wg_per_cu = cfg->append_wg_per_cu ? cfg->append_wg_per_cu : 2;
+  ctx->append_min_steps = cfg->append_min_steps ? cfg->append_min_steps : 4;
   *out = ctx.release();
   return HEDDLE_OK;
 }
@@ -532,6 +536,47 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   return HEDDLE_OK;
 }
 
+int heddle_plan_append_split(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
+                             const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_split_plan* plan) {
+  if (ctx == nullptr || plan == nullptr || ctx_len_host == nullptr || cu_chunk_host == nullptr || B < 1)
+    return HEDDLE_E_INVAL;
+  if (!plan->tile_b || !plan->tile_row0 || !plan->tile_rows_n || !plan->tile_extent || !plan->tile_nsplit ||
+      !plan->tile_part_base || !plan->item_tile || !plan->item_k || !plan->item_step_begin || !plan->item_step_end)
+    return HEDDLE_E_INVAL;
+  if (cu_chunk_host[0] != 0) return HEDDLE_E_INVAL;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t C = static_cast<int64_t>(cu_chunk_host[b + 1]) - cu_chunk_host[b];
+    if (C < 1 || ctx_len_host[b] < 0 || ctx_len_host[b] + C > HEDDLE_MAX_CONTEXT) return HEDDLE_E_INVAL;
+  }
+  if (tile_rows <= 0) tile_rows = append_tile_rows(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads);
+  if (tile_rows < 1) tile_rows = 1;
+  std::vector<AppendTile> tiles;
+  plan_append(B, ctx_len_host, cu_chunk_host, tile_rows, tiles);
+  AppendSplit sp;
+  split_append_tiles(ctx->plan, ctx->append_wg_per_cu, ctx->append_min_steps, tiles, ctx_len_host, sp);
+  if (static_cast<int64_t>(tiles.size()) > plan->cap_tiles || static_cast<int64_t>(sp.items.size()) > plan->cap_items)
+    return HEDDLE_E_NOMEM;
+  plan->n_tiles = static_cast<int32_t>(tiles.size());
+  plan->n_items = static_cast<int32_t>(sp.items.size());
+  plan->n_slots = sp.n_slots;
+  plan->tile_rows = tile_rows;
+  for (size_t t = 0; t < tiles.size(); ++t) {
+    plan->tile_b[t] = tiles[t].b;
+    plan->tile_row0[t] = tiles[t].row0;
+    plan->tile_rows_n[t] = tiles[t].rows;
+    plan->tile_extent[t] = tiles[t].extent;
+    plan->tile_nsplit[t] = sp.nsplit[t];
+    plan->tile_part_base[t] = sp.part_base[t];
+  }
+  for (size_t i = 0; i < sp.items.size(); ++i) {
+    plan->item_tile[i] = sp.items[i].tile;
+    plan->item_k[i] = sp.items[i].k;
+    plan->item_step_begin[i] = sp.items[i].step_begin;
+    plan->item_step_end[i] = sp.items[i].step_end;
+  }
+  return HEDDLE_OK;
+}
+
 int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
   {
     const int rc_args = check_decode_args(ctx, args);
@@ -657,28 +702,57 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
   plan_append(B, args->ctx_len_host, args->cu_chunk_host, append_tile_rows(G), ctx->tiles);
-  const size_t n_tiles = ctx->tiles.size();
+  AppendSplit& sp = ctx->split;
+  split_append_tiles(ctx->plan, ctx->append_wg_per_cu, ctx->append_min_steps, ctx->tiles, args->ctx_len_host, sp);
+  const size_t n_items = sp.items.size();
   const int32_t n_rows = args->cu_chunk_host[B];
+  const bool any_split = sp.n_slots > 0;
+  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
 
-  // plan image: ctx_len[B] | cu_chunk[B+1] | 4 x tiles
-  const size_t words = 2 * static_cast<size_t>(B) + 1 + 4 * n_tiles;
+  int rc = HEDDLE_OK;
+  if (any_split) {
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems,
+                     static_cast<size_t>(sp.n_slots) * Hq * D, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems,
+                     static_cast<size_t>(sp.n_slots) * Hq * 4, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+  }
+
+  // plan image: item records | ctx_len[B] | cu_chunk[B+1] | row records (only if some tile is split)
+  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 1 + (any_split ? 2 * static_cast<size_t>(n_rows) : 0);
   StagingSlot* slot = nullptr;
-  int rc = acquire_slot(ctx, words, &slot);
+  rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
   int32_t* w = slot->host;
-  int32_t* h_len = w;
+  AppendItemRec* h_items = reinterpret_cast<AppendItemRec*>(w);
+  int32_t* h_len = w + 8 * n_items;
   int32_t* h_cu = h_len + B;
-  int32_t* h_tb = h_cu + B + 1;
-  int32_t* h_tr0 = h_tb + n_tiles;
-  int32_t* h_trn = h_tr0 + n_tiles;
-  int32_t* h_tex = h_trn + n_tiles;
+  DecodeTrajRec* h_rows = reinterpret_cast<DecodeTrajRec*>(h_cu + B + 1);
   std::memcpy(h_len, args->ctx_len_host, sizeof(int32_t) * B);
   std::memcpy(h_cu, args->cu_chunk_host, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
-  for (size_t i = 0; i < n_tiles; ++i) {
-    h_tb[i] = ctx->tiles[i].b;
-    h_tr0[i] = ctx->tiles[i].row0;
-    h_trn[i] = ctx->tiles[i].rows;
-    h_tex[i] = ctx->tiles[i].extent;
+  for (size_t i = 0; i < n_items; ++i) {
+    const AppendItem& it = sp.items[i];
+    const AppendTile& tl = ctx->tiles[static_cast<size_t>(it.tile)];
+    AppendItemRec& r = h_items[i];
+    r.b = tl.b;
+    r.row0 = tl.row0;
+    r.rows_n = tl.rows;
+    r.key_end = std::min(tl.extent, it.step_end * kAppendStepKeys);
+    r.step_begin = it.step_begin;
+    r.nsplit = sp.nsplit[static_cast<size_t>(it.tile)];
+    r.slot0 = sp.part_base[static_cast<size_t>(it.tile)] + it.k;
+    r.pad = 0;
+  }
+  if (any_split) {
+    for (size_t t = 0; t < ctx->tiles.size(); ++t) {
+      const AppendTile& tl = ctx->tiles[t];
+      const int32_t first_row = args->cu_chunk_host[tl.b] + tl.row0;
+      for (int32_t r = 0; r < tl.rows; ++r) {
+        h_rows[first_row + r].part_off = sp.part_base[t] + r * sp.nsplit[t];
+        h_rows[first_row + r].nsplit = sp.nsplit[t];
+      }
+    }
   }
   rc = upload(ctx, slot, words, stream);
   if (rc != HEDDLE_OK) return rc;
@@ -708,14 +782,13 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   al.block_ids = args->block_ids;
   al.ctx_len = d + (h_len - w);
   al.cu_chunk = d + (h_cu - w);
-  al.tile_b = d + (h_tb - w);
-  al.tile_row0 = d + (h_tr0 - w);
-  al.tile_rows_n = d + (h_trn - w);
-  al.tile_extent = d + (h_tex - w);
+  al.items = reinterpret_cast<const AppendItemRec*>(d);
+  al.part_acc = ctx->dev_part_acc;
+  al.part_ml = ctx->dev_part_ml;
   al.q = static_cast<const uint16_t*>(args->q);
   al.out = static_cast<uint16_t*>(args->out);
   al.lse = args->lse;
-  al.n_tiles = static_cast<int32_t>(n_tiles);
+  al.n_items = static_cast<int32_t>(n_items);
   al.n_q_heads = ctx->cfg.n_q_heads;
   al.n_kv_heads = ctx->cfg.n_kv_heads;
   al.head_dim = ctx->cfg.head_dim;
@@ -723,6 +796,20 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   {
     TimedScope t(ctx, 2, stream);
     HEDDLE_HIP(launch_append_attn(al, stream));
+  }
+  if (any_split) {          // merge the parts of every row of a split tile; rows of other tiles are final
+    DecodeLaunch dl{};
+    dl.trajs = reinterpret_cast<const DecodeTrajRec*>(d + (reinterpret_cast<int32_t*>(h_rows) - w));
+    dl.part_acc = ctx->dev_part_acc;
+    dl.part_ml = ctx->dev_part_ml;
+    dl.out = static_cast<uint16_t*>(args->out);
+    dl.lse = args->lse;
+    dl.B = n_rows;
+    dl.n_q_heads = Hq;
+    dl.n_kv_heads = ctx->cfg.n_kv_heads;
+    dl.head_dim = D;
+    TimedScope t(ctx, 1, stream);
+    HEDDLE_HIP(launch_decode_combine(dl, stream));
   }
   return HEDDLE_OK;
 }

@@ -53,7 +53,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// Launch = AppendLaunch: causal chunk rows of one trajectory, final bf16 output.
+// Launch = AppendLaunch: causal chunk rows of one trajectory against all their keys (final bf16
+// output) or against one part of them (split-K partial, merged by decode_combine_kernel).
 // Launch = GroupLaunch: the decode queries of the trajectories of a group against a range of the
 // blocks they share (whole blocks, every key visible to every row), split-K partial output.
 template <int G, int D, typename Launch>
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   const int r_in_tile = n_global - g * R;
   const int head = h * G + g;
 
-  int rows_n, extent, kv_len, edge, pos, part = 0;
+  int rows_n, extent, kv_len, edge, pos, part = 0, nsplit = 1;
   int64_t q_row;
   const int32_t* table;
   if constexpr (kGroup) {
@@ -102,17 +103,21 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
     edge = extent - 1;
     part = a.trajs[q_row].part_off + rec.part;
   } else {
-    const int b = a.tile_b[tile];
-    const int row0 = a.tile_row0[tile];
-    rows_n = a.tile_rows_n[tile];
-    extent = a.tile_extent[tile];          // keys visible to the tile's last row
+    const AppendItemRec rec = a.items[tile];
+    const int b = rec.b;
+    const int row0 = rec.row0;
+    rows_n = rec.rows_n;
+    const int key0 = rec.step_begin * kChunkTokens;   // keys are counted from the item's first step
+    extent = rec.key_end - key0;
     const int L = a.ctx_len[b];
-    kv_len = L + (a.cu_chunk[b + 1] - a.cu_chunk[b]);
-    table = a.block_ids + a.row_off[b];
+    kv_len = L + (a.cu_chunk[b + 1] - a.cu_chunk[b]) - key0;
+    table = a.block_ids + a.row_off[b] + rec.step_begin * kChunkBlocks;
     const int chunk_row = row0 + min(r_in_tile, rows_n - 1);
     q_row = static_cast<int64_t>(a.cu_chunk[b]) + chunk_row;
-    pos = L + chunk_row;                   // last key this row may see
-    edge = L + row0;                       // first position at which some row of the tile is masked
+    pos = L + chunk_row - key0;            // last key this row may see
+    edge = L + row0 - key0;                // first position at which some row of the tile is masked
+    nsplit = rec.nsplit;
+    part = rec.slot0 + min(r_in_tile, rows_n - 1) * nsplit;
   }
   const bool row_valid = r_in_tile < rows_n;
 
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
 
   // ---- normalise and store: register j of tile mt is head-dim element mt*32 + 8*(j/4) + 4*hi + j%4
   l_sum += __shfl_xor(l_sum, 32, 64);
-  if constexpr (kGroup) {
+  if (kGroup || nsplit > 1) {
     if (row_valid) {
       const int64_t slot = static_cast<int64_t>(part) * a.n_q_heads + head;
       float* ap = a.part_acc + slot * D;
@@ -297,26 +302,28 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
       // for the output's denominator and for the log-sum-exp of this part
       if (hi == 0) *reinterpret_cast<float4*>(a.part_ml + slot * 4) = float4{m_ref, l_sum, l_sum, 0.0f};
     }
-  } else if (row_valid) {
-    const float inv = 1.0f / l_sum;
-    uint16_t* op = a.out + (q_row * a.n_q_heads + head) * D;
+  } else if constexpr (!kGroup) {
+    if (row_valid) {
+      const float inv = 1.0f / l_sum;
+      uint16_t* op = a.out + (q_row * a.n_q_heads + head) * D;
 #pragma unroll
-    for (int mt = 0; mt < NMT; ++mt)
+      for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
-      for (int jq = 0; jq < 4; ++jq) {
-        u32x2 w;
-        w.x = pack_bf16(o[mt][4 * jq + 0] * inv, o[mt][4 * jq + 1] * inv);
-        w.y = pack_bf16(o[mt][4 * jq + 2] * inv, o[mt][4 * jq + 3] * inv);
-        *reinterpret_cast<u32x2*>(op + mt * 32 + 8 * jq + 4 * hi) = w;
-      }
-    if (a.lse != nullptr && hi == 0)
-      a.lse[q_row * a.n_q_heads + head] = (m_ref + __builtin_log2f(l_sum)) * 0.6931471805599453f;
+        for (int jq = 0; jq < 4; ++jq) {
+          u32x2 w;
+          w.x = pack_bf16(o[mt][4 * jq + 0] * inv, o[mt][4 * jq + 1] * inv);
+          w.y = pack_bf16(o[mt][4 * jq + 2] * inv, o[mt][4 * jq + 3] * inv);
+          *reinterpret_cast<u32x2*>(op + mt * 32 + 8 * jq + 4 * hi) = w;
+        }
+      if (a.lse != nullptr && hi == 0)
+        a.lse[q_row * a.n_q_heads + head] = (m_ref + __builtin_log2f(l_sum)) * 0.6931471805599453f;
+    }
   }
 }
 
 template <int G, int D>
 hipError_t launch_append_t(const AppendLaunch& a, hipStream_t stream) {
-  const dim3 grid(static_cast<unsigned>(a.n_tiles) * static_cast<unsigned>(a.n_kv_heads));
+  const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
   hipLaunchKernelGGL((append_attn_kernel<G, D, AppendLaunch>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }

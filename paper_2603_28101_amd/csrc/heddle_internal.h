@@ -61,4 +61,18 @@ struct AppendTile {
 void plan_append(int32_t B, const int32_t* ctx_len, const int32_t* cu_chunk, int32_t tile_rows,
                  std::vector<AppendTile>& tiles);
 
+// Split-K of an append batch that is too small to fill the GPU: the keys of a tile are cut at
+// multiples of 64 (one main-loop step of the kernel) into parts (rule in heddle.h).
+constexpr int32_t kAppendStepKeys = 64;
+struct AppendItem {
+  int32_t tile, k, step_begin, step_end;
+};
+struct AppendSplit {
+  std::vector<int32_t> nsplit, part_base;   // per tile, in plan order
+  int32_t n_slots = 0;
+  std::vector<AppendItem> items;            // longest first
+};
+void split_append_tiles(const PlanParams& p, int32_t append_wg_per_cu, int32_t min_steps,
+                        const std::vector<AppendTile>& tiles, const int32_t* ctx_len, AppendSplit& out);
+
 }  // namespace heddle

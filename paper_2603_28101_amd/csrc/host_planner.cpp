@@ -183,4 +183,52 @@ void plan_append(int32_t B, const int32_t* ctx_len, const int32_t* cu_chunk, int
                    [](const AppendTile& x, const AppendTile& y) { return x.extent > y.extent; });
 }
 
+void split_append_tiles(const PlanParams& p, int32_t append_wg_per_cu, int32_t min_steps,
+                        const std::vector<AppendTile>& tiles, const int32_t* ctx_len, AppendSplit& out) {
+  const size_t n = tiles.size();
+  out.nsplit.assign(n, 1);
+  out.part_base.assign(n, 0);
+  out.items.clear();
+  out.n_slots = 0;
+  std::vector<int64_t> steps(n), per(n);
+  int64_t work = 0;
+  for (size_t t = 0; t < n; ++t) {
+    steps[t] = per[t] = ceil_div(tiles[t].extent, kAppendStepKeys);
+    work += steps[t];
+  }
+  const int64_t slots = static_cast<int64_t>(p.n_cu) * append_wg_per_cu;
+  if (static_cast<int64_t>(n) * p.n_kv_heads < slots) {
+    const int64_t target = std::max<int64_t>(1, slots / p.n_kv_heads);
+    const int64_t chunk = std::max<int64_t>(ceil_div(work, target), min_steps);
+    for (size_t t = 0; t < n; ++t) {
+      const int64_t want = std::min<int64_t>(ceil_div(steps[t], chunk), p.max_split);
+      const int64_t each = ceil_div(steps[t], want);
+      int64_t parts = ceil_div(steps[t], each);
+      // the first row of the tile must see a key of the last part
+      const int64_t first_row_pos = static_cast<int64_t>(ctx_len[tiles[t].b]) + tiles[t].row0;
+      if (parts > 1 && (parts - 1) * each * kAppendStepKeys > first_row_pos) --parts;
+      out.nsplit[t] = static_cast<int32_t>(parts);
+      per[t] = each;
+    }
+  }
+  for (size_t t = 0; t < n; ++t) {
+    const int32_t parts = out.nsplit[t];
+    if (parts > 1) {
+      out.part_base[t] = out.n_slots;
+      out.n_slots += tiles[t].rows * parts;
+    }
+    for (int32_t k = 0; k < parts; ++k) {
+      AppendItem it;
+      it.tile = static_cast<int32_t>(t);
+      it.k = k;
+      it.step_begin = static_cast<int32_t>(k * per[t]);
+      it.step_end = static_cast<int32_t>(k == parts - 1 ? steps[t] : (k + 1) * per[t]);
+      out.items.push_back(it);
+    }
+  }
+  std::stable_sort(out.items.begin(), out.items.end(), [](const AppendItem& x, const AppendItem& y) {
+    return (x.step_end - x.step_begin) > (y.step_end - y.step_begin);
+  });
+}
+
 }  // namespace heddle

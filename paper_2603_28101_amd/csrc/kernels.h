@@ -60,6 +60,21 @@ struct KvWriteLaunch {
 };
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream);
 
+// One work item of the append pass (32-byte record): 128/G consecutive chunk rows of one
+// trajectory against a range of the keys they see.  An item that covers all keys of its tile
+// (nsplit == 1) writes the final rows; otherwise it writes a split-K partial per (row, head) into
+// slot slot0 + row_in_tile * nsplit, and decode_combine_kernel merges the parts of each row.
+struct AppendItemRec {
+  int32_t b;            // trajectory
+  int32_t row0;         // first chunk row of the tile
+  int32_t rows_n;       // rows in the tile
+  int32_t key_end;      // keys [64 * step_begin, key_end) are processed (key_end <= L_b + row0 + rows_n)
+  int32_t step_begin;   // first 64-key step of the item
+  int32_t slot0;        // partial slot of row 0 of the tile for this part
+  int32_t nsplit;       // parts of the tile
+  int32_t pad;
+};
+
 // Arguments of the causal chunked-append attention pass.  All pointers are device memory.
 struct AppendLaunch {
   const uint16_t* pool;
@@ -67,14 +82,13 @@ struct AppendLaunch {
   const int32_t* block_ids;
   const int32_t* ctx_len;      // [B]   tokens retained before the chunk
   const int32_t* cu_chunk;     // [B+1] prefix sums of chunk lengths
-  const int32_t* tile_b;       // [n_tiles] plan arrays, longest tile first
-  const int32_t* tile_row0;
-  const int32_t* tile_rows_n;
-  const int32_t* tile_extent;
+  const AppendItemRec* items;  // [n_items] longest first
   const uint16_t* q;           // bf16 [sum C][n_q][d]
   uint16_t* out;               // bf16 [sum C][n_q][d]
   float* lse;                  // f32 [sum C][n_q] or nullptr
-  int32_t n_tiles, n_q_heads, n_kv_heads, head_dim;
+  float* part_acc;             // as in DecodeLaunch; used by items with nsplit > 1
+  float* part_ml;
+  int32_t n_items, n_q_heads, n_kv_heads, head_dim;
   float scale_log2;
 };
 // One shared-prefix work item: the query rows of up to 128/G member trajectories of a group

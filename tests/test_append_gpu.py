@@ -178,3 +178,47 @@ def test_full_size_append_workload_sampled():
     assert_lse_close(lse[rows], ref_lse[rows], "append workload lse")
     # the whole chunk is in the pool, bit for bit, and nothing else changed
     assert np.array_equal(dc.pool_bits(), pool)
+
+
+# ------------------------------------------------------------------ small batches: split-K over the keys
+
+def test_single_long_trajectory_short_chunk_is_split_and_exact():
+    """One trajectory of 40 000 tokens with an 8-token chunk: one tile, cut into many parts."""
+    c = small(31, [40000], [8], 8, 2, 128)
+    dc = DeviceCase(c)
+    sp = dc.ctx.plan_append_split(c["lens"], c["cu_chunk"])
+    assert sp["n_tiles"] == 1 and sp["tile_nsplit"][0] > 8
+    out, lse = dc.append()
+    _, ref, ref_lse, spread = oracle_append(c)
+    assert_close(out, ref, "split append", spread)
+    assert_lse_close(lse, ref_lse, "split append lse")
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (16, 2), (32, 8)])
+def test_short_multi_token_decode(n_q, n_kv):
+    """A verify step of speculative decoding: 2-8 new tokens on each of a few trajectories of very
+    different lengths (ragged parts, L = 0 among them); default plan and one forced into many parts."""
+    L = [0, 1, 63, 64, 65, 1000, 4097, 20000]
+    C = [8, 2, 3, 5, 8, 4, 7, 6]
+    c = small(32, L, C, n_q, n_kv, 128)
+    _, ref, ref_lse, spread = oracle_append(c)
+    for kw in (dict(), dict(n_cu=1024, append_min_steps=1, max_split=64), dict(n_cu=16, max_split=3)):
+        dc = DeviceCase(c, **kw)
+        out, lse = dc.append()
+        assert_close(out, ref, f"multi-token decode {kw}", spread)
+        assert_lse_close(lse, ref_lse, f"multi-token decode lse {kw}")
+
+
+def test_split_parts_meet_the_causal_edge():
+    """Chunks long enough that the last part holds the whole causal triangle of a tile, with part
+    boundaries right at and around the first row's position."""
+    L = [64 * 7, 64 * 7 - 1, 64 * 7 + 1, 200]
+    C = [40, 33, 64, 130]
+    c = small(33, L, C, 8, 2, 128)
+    _, ref, ref_lse, spread = oracle_append(c)
+    dc = DeviceCase(c, n_cu=512, append_min_steps=1, max_split=64)
+    sp = dc.ctx.plan_append_split(c["lens"], c["cu_chunk"])
+    assert (sp["tile_nsplit"] > 1).any()
+    out, lse = dc.append()
+    assert_close(out, ref, "parts at the causal edge", spread)
+    assert_lse_close(lse, ref_lse, "parts at the causal edge lse")

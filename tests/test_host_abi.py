@@ -300,3 +300,28 @@ def test_placement_errors():
         heddle.placement_dp([3, 2, 1], 2, F, counts=[1, 0, 1])
     with pytest.raises(heddle.HeddleError):
         heddle.interference_table([2, 2], [1.0, 2.0], 4)
+
+
+# ------------------------------------------------------------------ split-K of small append batches
+
+def test_append_split_matches_oracle():
+    rng = np.random.default_rng(31)
+    for trial in range(80):
+        B = int(rng.integers(1, 6))
+        L = rng.integers(0, 20000, B).astype(np.int32)
+        Cn = rng.integers(1, 70, B)
+        cu = np.concatenate([[0], np.cumsum(Cn)]).astype(np.int32)
+        G = int(rng.choice([1, 4, 8]))
+        n_kv = int(rng.choice([1, 2, 8]))
+        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 3)),
+                   append_min_steps=int(rng.choice([1, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
+        c = heddle.Context(n_kv * G, n_kv, 128, 4, **prm)
+        got = c.plan_append_split(L, cu)
+        plan = op.plan_append(L, Cn, 128 // G)
+        ref = op.split_append_tiles(plan, L, n_kv, n_cu=prm["n_cu"], append_wg_per_cu=prm["append_wg_per_cu"],
+                                    min_steps=prm["append_min_steps"], max_split=prm["max_split"])
+        assert got["n_slots"] == ref["n_slots"] and got["n_items"] == ref["n_items"]
+        for k in ("tile_b", "tile_row0", "tile_rows_n", "tile_extent"):
+            assert np.array_equal(got[k], plan[k]), k
+        for k in ("tile_nsplit", "tile_part_base", "item_tile", "item_k", "item_step_begin", "item_step_end"):
+            assert np.array_equal(got[k], ref[k]), (trial, k)

@@ -312,3 +312,69 @@ def test_shared_plan_named_workload():
     assert sorted(plan["group_prefix"].tolist()) == sorted((prompt // 16).tolist())
     assert (np.diff(plan["member_off"]) == 16).all()
     check_shared_invariants(lens, row_off, ids, plan, 32, 4, 64, 4)
+
+
+# ------------------------------------------------------------- split-K of small append batches
+
+def test_append_split_hand_example():
+    # one trajectory, L = 1000, C = 5, tile height 32: one tile, extent 1005 -> S = 16 steps.
+    # n_kv = 2, n_cu = 4, 2 per CU: slots 8 > 1*2 tiles -> split.  W = 16, target = 8 // 2 = 4,
+    # chunk = max(ceil(16/4), 2) = 4; ns = 4, per = 4, n = 4; last part starts at key 3*4*64 = 768
+    # <= 1000 -> stays 4.  Slots: 5 rows * 4 parts = 20.
+    plan = op.plan_append([1000], [5], 32)
+    sp = op.split_append_tiles(plan, [1000], 2, n_cu=4, append_wg_per_cu=2, min_steps=2, max_split=8)
+    assert sp["tile_nsplit"].tolist() == [4] and sp["tile_part_base"].tolist() == [0] and sp["n_slots"] == 20
+    assert sp["item_k"].tolist() == [0, 1, 2, 3]
+    assert sp["item_step_begin"].tolist() == [0, 4, 8, 12] and sp["item_step_end"].tolist() == [4, 8, 12, 16]
+    # L = 60, C = 100 (tile rows 0-31: extent 92 -> 2 steps; rows 32-63: extent 124 -> 2; 64-95: 156 -> 3;
+    # 96-99: extent 160 -> 3 steps).  With chunk 1 the tile of rows 0-31 would get 2 parts, the second
+    # starting at key 64 > L + row0 = 60: merged back into one; rows 64-95 would get 3, the third
+    # starting at key 128 > 124: two.
+    plan = op.plan_append([60], [100], 32)
+    sp = op.split_append_tiles(plan, [60], 1, n_cu=64, append_wg_per_cu=2, min_steps=1, max_split=8)
+    by_row0 = {int(r): int(n) for r, n in zip(plan["tile_row0"], sp["tile_nsplit"])}
+    assert by_row0 == {0: 1, 32: 2, 64: 2, 96: 3}
+
+
+def test_append_split_invariants():
+    rng = np.random.default_rng(21)
+    for trial in range(80):
+        B = int(rng.integers(1, 6))
+        L = rng.integers(0, 20000, B)
+        C = rng.integers(1, 70, B)
+        R = int(rng.choice([16, 32, 128]))
+        n_kv = int(rng.choice([1, 2, 8]))
+        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 3)),
+                   min_steps=int(rng.choice([1, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
+        plan = op.plan_append(L, C, R)
+        sp = op.split_append_tiles(plan, L, n_kv, **prm)
+        used = np.zeros(sp["n_slots"], dtype=np.int32)
+        for t in range(plan["n_tiles"]):
+            S = -(-int(plan["tile_extent"][t]) // 64)
+            n = int(sp["tile_nsplit"][t])
+            assert 1 <= n <= prm["max_split"]
+            parts = sorted((int(k), int(lo), int(hi)) for tt, k, lo, hi in
+                           zip(sp["item_tile"], sp["item_k"], sp["item_step_begin"], sp["item_step_end"]) if tt == t)
+            assert [p[0] for p in parts] == list(range(n))
+            assert parts[0][1] == 0 and parts[-1][2] == S
+            assert all(parts[i][2] == parts[i + 1][1] and parts[i][1] < parts[i][2] for i in range(n - 1))
+            # the first row of the tile sees at least one key of every part
+            assert parts[-1][1] * 64 <= int(L[plan["tile_b"][t]]) + int(plan["tile_row0"][t])
+            if n > 1:
+                rows = int(plan["tile_rows_n"][t])
+                used[sp["tile_part_base"][t]: sp["tile_part_base"][t] + rows * n] += 1
+        assert (used == 1).all()
+        if plan["n_tiles"] * n_kv >= prm["n_cu"] * prm["append_wg_per_cu"]:
+            assert (sp["tile_nsplit"] == 1).all()
+        d = sp["item_step_end"] - sp["item_step_begin"]
+        assert (np.diff(d) <= 0).all()
+
+
+def test_append_split_leaves_the_large_workload_alone_and_spreads_a_single_straggler():
+    L, C = hw.workload_lengths(5, 0)
+    plan = op.plan_append(L, C, 32)
+    sp = op.split_append_tiles(plan, L, 8)
+    assert (sp["tile_nsplit"] == 1).all() and sp["n_slots"] == 0
+    plan = op.plan_append([120000], [8], 32)
+    sp = op.split_append_tiles(plan, [120000], 8)
+    assert sp["tile_nsplit"][0] >= 32           # one tile x 8 kv heads alone would use 8 of 512 slots
