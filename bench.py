@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8])
     ap.add_argument("--op", default="attention", choices=["attention", "pack", "placement"],
                     help="attention: the workload's decode or append pass (default); pack: gather of every "
                          "trajectory's blocks into one contiguous staging buffer (whole-block copy); placement: decode step time per batch size -> interference table -> "
@@ -119,7 +119,9 @@ def main():
         def step():
             ctx.attn_append(L, cu, case["row_off"], row_off, block_ids, q, k_new, v_new, out, None, stream=stream)
 
-        dominant, bound = 2, "mfma"
+        # below the machine balance (flops per byte of K/V) the pass is priced in bytes
+        dominant = 2
+        bound = "mfma" if unit_flops / unit_bytes > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBPS else "hbm"
 
     torch.cuda.synchronize()
     for _ in range(args.warmup):
@@ -142,6 +144,7 @@ def main():
     kernel_us, n_launch = ctx.timing_read(dominant)
     aux_us = ctx.timing_read({"decode": 1, "append": 3, "pack": 5}[kind])[0]
     group_us = ctx.timing_read(6)[0] if shared else 0.0
+    ctx_combine_us = ctx.timing_read(1)[0]
     ctx.timing_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -164,6 +167,15 @@ def main():
         if shared:
             roofline["kernel_bytes"] = private_bytes
             roofline["shared_prefix_kernel_avg_us"] = round(group_us, 2)
+    elif bound == "hbm":
+        value = unit_bytes / (ms_per_step * 1e-3) / 1e9
+        metric, unit = "append-attention KV GB/s", "GB/s"
+        achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
+        roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "kernel": "append_attn_kernel", "kernel_avg_us": round(kernel_us, 2),
+                    "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2),
+                    "combine_avg_us": round(ctx_combine_us, 2), "flops_per_step": unit_flops}
     else:
         value = unit_flops / (ms_per_step * 1e-3) / 1e12
         metric, unit = "append-attention TFLOP/s", "TFLOP/s"

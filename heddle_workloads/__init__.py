@@ -46,6 +46,8 @@ WORKLOADS = {
     4: Workload(4, "straggler-decode", "decode", 256, 32, 8, 128),
     5: Workload(5, "tool-append", "append", 32, 32, 8, 128),
     6: Workload(6, "grpo-group-decode", "decode", 128, 32, 8, 128),
+    7: Workload(7, "verify-4-tokens", "append", 64, 32, 8, 128),
+    8: Workload(8, "straggler-append", "append", 1, 32, 8, 128),
 }
 
 GROUP_SAMPLES = 16   # samples per prompt (Sec. 7, Workloads)
@@ -95,6 +97,10 @@ def draw_lengths(cfg_id: int, rng: np.random.Generator):
         return L, C
     if cfg_id == 6:
         return draw_group_lengths(rng)[0], None
+    if cfg_id == 7:   # the lengths of workload 2, four new tokens each (a speculative-decoding verify step)
+        return _lognormal_lengths(rng, 64, 4096, 1.0, 256, 32768), np.full(64, 4, dtype=np.int64)
+    if cfg_id == 8:   # one long-tail trajectory alone on the GPU receives a short tool output
+        return rng.integers(100000, 120001, 1).astype(np.int64), rng.integers(32, 65, 1).astype(np.int64)
     raise ValueError(f"unknown workload {cfg_id}")
 
 

@@ -145,14 +145,14 @@ int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_
                        const int32_t* cu_chunk_host, int32_t tile_rows, heddle_append_plan* plan);
 
 /* ---- split-K of a small append batch (host only) ------------------------------
- * An append batch with few tiles (one long trajectory with a short chunk; the
- * verify step of speculative decoding, a few tokens per trajectory, Sec. 8) would
- * leave most of the GPU idle; the keys of its tiles are then cut into parts that
- * run as separate work items and are merged per row afterwards.  Rule (integer),
- * tiles as produced by heddle_plan_append, index t in that order:
- *  1. S_t = ceil(extent_t / 64); slots = n_cu * append_wg_per_cu; if
- *     n_tiles * n_kv_heads >= slots nothing is split.
- *  2. else W = sum S_t, target = max(1, slots / n_kv_heads), chunk = max(ceil(W /
+ * A tile with many more keys than an even share of the batch (one long trajectory
+ * with a short chunk; the long tail of a speculative-decoding verify step, a few
+ * tokens per trajectory, Sec. 8) would keep one workgroup busy long after the rest;
+ * its keys are cut into parts that run as separate work items and are merged per
+ * row afterwards, as in decode.  Rule (integer), tiles as produced by
+ * heddle_plan_append, index t in that order:
+ *  1. S_t = ceil(extent_t / 64); slots = n_cu * append_wg_per_cu.
+ *  2. W = sum S_t, target = max(1, slots / n_kv_heads), chunk = max(ceil(W /
  *     target), append_min_steps); per tile ns = min(ceil(S/chunk), max_split), per =
  *     ceil(S/ns), n = ceil(S/per); if n > 1 and (n-1)*per*64 > L_b + row0 then n -= 1
  *     (the tile's first row must see a key of the last part).  Part k < n-1 covers

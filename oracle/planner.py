@@ -231,14 +231,14 @@ APPEND_STEP_KEYS = 64     # keys per main-loop step of the append kernel; parts 
 
 def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_cu=2, min_steps=4,
                        max_split=64):
-    """Split-K for an append batch too small to fill the GPU (one long trajectory with a short
-    chunk; a speculative-decoding verify step of a few tokens per trajectory, Sec. 8): the keys
-    of a tile are cut into parts that run as separate work items and are merged afterwards.
+    """Split-K for append: a tile whose keys are many more than an even share of the batch (one
+    long trajectory with a short chunk; the long tail of a speculative-decoding verify step of a
+    few tokens per trajectory, Sec. 8) has its keys cut into parts that run as separate work
+    items and are merged afterwards, as in decode.
 
     Rule (integer; `plan` is the output of plan_append, tiles in its order, index t):
-      1. S_t = ceil(extent_t / 64) steps.  slots = n_cu * append_wg_per_cu.  If
-         n_tiles * n_kv_heads >= slots nothing is split (nsplit_t = 1 for all t).
-      2. Otherwise W = sum S_t, target = max(1, slots // n_kv_heads),
+      1. S_t = ceil(extent_t / 64) steps; slots = n_cu * append_wg_per_cu.
+      2. W = sum S_t, target = max(1, slots // n_kv_heads),
          chunk = max(ceil(W / target), min_steps).  Per tile ns = min(ceil(S/chunk), max_split),
          per = ceil(S / ns), n = ceil(S / per); if n > 1 and (n-1) * per * 64 > L_b + row0 then
          n -= 1 (the first row of the tile must see a key of the last part).  Part k < n-1
@@ -252,18 +252,17 @@ def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_
     S = [_ceil_div(int(e), APPEND_STEP_KEYS) for e in plan["tile_extent"]]
     slots = n_cu * append_wg_per_cu
     nsplit, per_of = [1] * n_tiles, list(S)
-    if n_tiles * n_kv_heads < slots:
-        W = sum(S)
-        target = max(1, slots // n_kv_heads)
-        chunk = max(_ceil_div(W, target), min_steps)
-        for t in range(n_tiles):
-            ns = min(_ceil_div(S[t], chunk), max_split)
-            per = _ceil_div(S[t], ns)
-            n = _ceil_div(S[t], per)
-            first_row_pos = int(ctx_lens[int(plan["tile_b"][t])]) + int(plan["tile_row0"][t])
-            if n > 1 and (n - 1) * per * APPEND_STEP_KEYS > first_row_pos:
-                n -= 1
-            nsplit[t], per_of[t] = n, per
+    W = sum(S)
+    target = max(1, slots // n_kv_heads)
+    chunk = max(_ceil_div(W, target), min_steps)
+    for t in range(n_tiles):
+        ns = min(_ceil_div(S[t], chunk), max_split)
+        per = _ceil_div(S[t], ns)
+        n = _ceil_div(S[t], per)
+        first_row_pos = int(ctx_lens[int(plan["tile_b"][t])]) + int(plan["tile_row0"][t])
+        if n > 1 and (n - 1) * per * APPEND_STEP_KEYS > first_row_pos:
+            n -= 1
+        nsplit[t], per_of[t] = n, per
     base, part_base, items = 0, [], []
     for t in range(n_tiles):
         part_base.append(base if nsplit[t] > 1 else 0)

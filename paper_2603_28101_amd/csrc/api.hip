@@ -719,8 +719,13 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
     if (rc != HEDDLE_OK) return rc;
   }
 
-  // plan image: item records | ctx_len[B] | cu_chunk[B+1] | row records (only if some tile is split)
-  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 1 + (any_split ? 2 * static_cast<size_t>(n_rows) : 0);
+  // rows of split tiles: the combine pass runs over these only
+  size_t n_split_rows = 0;
+  for (size_t t = 0; t < ctx->tiles.size(); ++t)
+    if (sp.nsplit[t] > 1) n_split_rows += static_cast<size_t>(ctx->tiles[t].rows);
+
+  // plan image: item records | ctx_len[B] | cu_chunk[B+1] | records of the split rows | their row numbers
+  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 1 + 3 * n_split_rows;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
@@ -744,13 +749,17 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
     r.slot0 = sp.part_base[static_cast<size_t>(it.tile)] + it.k;
     r.pad = 0;
   }
-  if (any_split) {
+  int32_t* h_row_no = reinterpret_cast<int32_t*>(h_rows + n_split_rows);
+  {
+    size_t i = 0;
     for (size_t t = 0; t < ctx->tiles.size(); ++t) {
+      if (sp.nsplit[t] == 1) continue;
       const AppendTile& tl = ctx->tiles[t];
       const int32_t first_row = args->cu_chunk_host[tl.b] + tl.row0;
-      for (int32_t r = 0; r < tl.rows; ++r) {
-        h_rows[first_row + r].part_off = sp.part_base[t] + r * sp.nsplit[t];
-        h_rows[first_row + r].nsplit = sp.nsplit[t];
+      for (int32_t r = 0; r < tl.rows; ++r, ++i) {
+        h_rows[i].part_off = sp.part_base[t] + r * sp.nsplit[t];
+        h_rows[i].nsplit = sp.nsplit[t];
+        h_row_no[i] = first_row + r;
       }
     }
   }
@@ -800,11 +809,12 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   if (any_split) {          // merge the parts of every row of a split tile; rows of other tiles are final
     DecodeLaunch dl{};
     dl.trajs = reinterpret_cast<const DecodeTrajRec*>(d + (reinterpret_cast<int32_t*>(h_rows) - w));
+    dl.out_row = d + (h_row_no - w);
     dl.part_acc = ctx->dev_part_acc;
     dl.part_ml = ctx->dev_part_ml;
     dl.out = static_cast<uint16_t*>(args->out);
     dl.lse = args->lse;
-    dl.B = n_rows;
+    dl.B = static_cast<int32_t>(n_split_rows);
     dl.n_q_heads = Hq;
     dl.n_kv_heads = ctx->cfg.n_kv_heads;
     dl.head_dim = D;

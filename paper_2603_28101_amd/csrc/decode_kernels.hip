@@ -491,16 +491,18 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeLaunch a) {
   const int e = threadIdx.x;
   const int p0 = tr.part_off;
   float M = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 4]);
   float num = 0.0f, den = 0.0f, den_exact = 0.0f;
-  for (int s = 0; s < ns; ++s) {
+#pragma unroll 8
+  for (int s = 0; s < ns; ++s) {   // unrolled so that the loads of several parts are in flight together
     const int64_t pj = static_cast<int64_t>(p0 + s) * a.n_q_heads + j;
     const float f = __builtin_amdgcn_exp2f(a.part_ml[pj * 4] - M);
     den = fmaf(f, a.part_ml[pj * 4 + 1], den);
     den_exact = fmaf(f, a.part_ml[pj * 4 + 2], den_exact);
     num = fmaf(f, a.part_acc[pj * D + e], num);
   }
-  const int64_t oj = static_cast<int64_t>(b) * a.n_q_heads + j;
+  const int64_t oj = static_cast<int64_t>(a.out_row != nullptr ? a.out_row[b] : b) * a.n_q_heads + j;
   a.out[oj * D + e] = f32_to_bf16_rne(num / den);
   if (a.lse != nullptr && e == 0) a.lse[oj] = (M + __builtin_log2f(den_exact)) * 0.6931471805599453f;
 }

@@ -197,19 +197,17 @@ void split_append_tiles(const PlanParams& p, int32_t append_wg_per_cu, int32_t m
     work += steps[t];
   }
   const int64_t slots = static_cast<int64_t>(p.n_cu) * append_wg_per_cu;
-  if (static_cast<int64_t>(n) * p.n_kv_heads < slots) {
-    const int64_t target = std::max<int64_t>(1, slots / p.n_kv_heads);
-    const int64_t chunk = std::max<int64_t>(ceil_div(work, target), min_steps);
-    for (size_t t = 0; t < n; ++t) {
-      const int64_t want = std::min<int64_t>(ceil_div(steps[t], chunk), p.max_split);
-      const int64_t each = ceil_div(steps[t], want);
-      int64_t parts = ceil_div(steps[t], each);
-      // the first row of the tile must see a key of the last part
-      const int64_t first_row_pos = static_cast<int64_t>(ctx_len[tiles[t].b]) + tiles[t].row0;
-      if (parts > 1 && (parts - 1) * each * kAppendStepKeys > first_row_pos) --parts;
-      out.nsplit[t] = static_cast<int32_t>(parts);
-      per[t] = each;
-    }
+  const int64_t target = std::max<int64_t>(1, slots / p.n_kv_heads);
+  const int64_t chunk = std::max<int64_t>(ceil_div(work, target), min_steps);
+  for (size_t t = 0; t < n; ++t) {
+    const int64_t want = std::min<int64_t>(ceil_div(steps[t], chunk), p.max_split);
+    const int64_t each = ceil_div(steps[t], want);
+    int64_t parts = ceil_div(steps[t], each);
+    // the first row of the tile must see a key of the last part
+    const int64_t first_row_pos = static_cast<int64_t>(ctx_len[tiles[t].b]) + tiles[t].row0;
+    if (parts > 1 && (parts - 1) * each * kAppendStepKeys > first_row_pos) --parts;
+    out.nsplit[t] = static_cast<int32_t>(parts);
+    per[t] = each;
   }
   for (size_t t = 0; t < n; ++t) {
     const int32_t parts = out.nsplit[t];

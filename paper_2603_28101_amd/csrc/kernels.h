@@ -30,6 +30,7 @@ struct DecodeLaunch {
   const int32_t* block_ids;    // CSR block table
   const DecodeItemRec* items;  // [n_items] longest first
   const DecodeTrajRec* trajs;  // [B]
+  const int32_t* out_row;      // combine only: output row of record i, or nullptr for row i
   const uint16_t* q;           // bf16 [B][n_q][d]
   float* part_acc;             // f32 [n_parts][n_q][d]   unnormalised sum of p * v
   float* part_ml;              // f32 [n_parts][n_q][4]   (max logit in log2 units, sum of bf16-rounded p,
