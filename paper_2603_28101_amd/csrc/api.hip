@@ -478,10 +478,12 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     kw.block_ids = args->block_ids;
     kw.first_pos = d + (h_first - w);
     kw.cu_rows = d + (h_cu - w);
+    kw.cu_wblk = kw.cu_rows;                 // one row, hence one block, per trajectory
     kw.k = static_cast<const uint16_t*>(args->k_new);
     kw.v = static_cast<const uint16_t*>(args->v_new);
     kw.B = B;
     kw.n_rows = B;
+    kw.n_wblk = B;
     kw.n_kv_heads = ctx->cfg.n_kv_heads;
     kw.head_dim = D;
     TimedScope t(ctx, 3, stream);
@@ -642,10 +644,12 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     kw.block_ids = args->block_ids;
     kw.first_pos = d + (h_first - w);
     kw.cu_rows = d + (h_cu - w);
+    kw.cu_wblk = kw.cu_rows;                 // one row, hence one block, per trajectory
     kw.k = static_cast<const uint16_t*>(args->k_new);
     kw.v = static_cast<const uint16_t*>(args->v_new);
     kw.B = B;
     kw.n_rows = B;
+    kw.n_wblk = B;
     kw.n_kv_heads = ctx->cfg.n_kv_heads;
     kw.head_dim = D;
     TimedScope t(ctx, 3, stream);
@@ -724,8 +728,8 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   for (size_t t = 0; t < ctx->tiles.size(); ++t)
     if (sp.nsplit[t] > 1) n_split_rows += static_cast<size_t>(ctx->tiles[t].rows);
 
-  // plan image: item records | ctx_len[B] | cu_chunk[B+1] | records of the split rows | their row numbers
-  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 1 + 3 * n_split_rows;
+  // plan image: item records | ctx_len[B] | cu_chunk[B+1] | cu_wblk[B+1] | records of the split rows | their row numbers
+  const size_t words = 8 * n_items + 3 * static_cast<size_t>(B) + 2 + 3 * n_split_rows;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
@@ -733,7 +737,13 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   AppendItemRec* h_items = reinterpret_cast<AppendItemRec*>(w);
   int32_t* h_len = w + 8 * n_items;
   int32_t* h_cu = h_len + B;
-  DecodeTrajRec* h_rows = reinterpret_cast<DecodeTrajRec*>(h_cu + B + 1);
+  int32_t* h_wblk = h_cu + B + 1;
+  DecodeTrajRec* h_rows = reinterpret_cast<DecodeTrajRec*>(h_wblk + B + 1);
+  h_wblk[0] = 0;
+  for (int32_t b = 0; b < B; ++b) {          // pool blocks that receive the chunk's rows
+    const int32_t L = args->ctx_len_host[b], C = args->cu_chunk_host[b + 1] - args->cu_chunk_host[b];
+    h_wblk[b + 1] = h_wblk[b] + ((L + C - 1) / HEDDLE_BLOCK_TOKENS - L / HEDDLE_BLOCK_TOKENS + 1);
+  }
   std::memcpy(h_len, args->ctx_len_host, sizeof(int32_t) * B);
   std::memcpy(h_cu, args->cu_chunk_host, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
   for (size_t i = 0; i < n_items; ++i) {
@@ -775,10 +785,12 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
     kw.block_ids = args->block_ids;
     kw.first_pos = d + (h_len - w);
     kw.cu_rows = d + (h_cu - w);
+    kw.cu_wblk = d + (h_wblk - w);
     kw.k = static_cast<const uint16_t*>(args->k);
     kw.v = static_cast<const uint16_t*>(args->v);
     kw.B = B;
     kw.n_rows = n_rows;
+    kw.n_wblk = h_wblk[B];
     kw.n_kv_heads = ctx->cfg.n_kv_heads;
     kw.head_dim = ctx->cfg.head_dim;
     TimedScope t(ctx, 3, stream);

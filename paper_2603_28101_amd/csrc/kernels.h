@@ -55,9 +55,10 @@ struct KvWriteLaunch {
   const int32_t* block_ids;
   const int32_t* first_pos;    // [B] device
   const int32_t* cu_rows;      // [B+1] device
+  const int32_t* cu_wblk;      // [B+1] device: prefix sums of the pool blocks each trajectory's rows touch
   const uint16_t* k;           // bf16 [n_rows][n_kv][d]
   const uint16_t* v;
-  int32_t B, n_rows, n_kv_heads, head_dim;
+  int32_t B, n_rows, n_wblk, n_kv_heads, head_dim;
 };
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream);
 

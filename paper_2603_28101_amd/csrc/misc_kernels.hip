@@ -9,39 +9,64 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// One workgroup per new token row; thread t moves one 8-element piece of K (one 16-byte
-// store into the token-major K tile) and of V (eight 2-byte stores into the transposed V
-// tile, where the 16 tokens of a head-dim element are contiguous).
-// Row i of trajectory b (rows cu_rows[b] .. cu_rows[b+1]) goes to position first_pos[b] + i.
+// One workgroup per (pool block that receives new rows, kv head).  Trajectory b owns rows
+// cu_rows[b] .. cu_rows[b+1] and write blocks cu_wblk[b] .. cu_wblk[b+1]; its row i goes to token
+// position first_pos[b] + i.  K rows are copied as 16-byte pieces into the token-major K tile.
+// V rows pass through LDS and leave transposed: a thread assembles the 8 consecutive tokens of
+// one head-dim element and stores them as one 16-byte piece of the [d][16] V tile; where the new
+// rows cover only part of those 8 slots the piece is read, merged and written back (the other
+// slots belong to the same trajectory and nobody else writes this block during the call).
 __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
-  const int row = blockIdx.x;
-  // trajectory of this row: last b with cu_rows[b] <= row
-  int lo = 0, hi = a.B;
+  constexpr int kMaxD = 128;
+  __shared__ __attribute__((aligned(16))) uint16_t s_v[16][kMaxD + 8];
+  const int wb = blockIdx.x / a.n_kv_heads;
+  const int h = blockIdx.x - wb * a.n_kv_heads;
+  int lo = 0, hi = a.B;                       // trajectory of this write block: last b with cu_wblk[b] <= wb
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (a.cu_rows[mid] <= row) lo = mid; else hi = mid;
+    if (a.cu_wblk[mid] <= wb) lo = mid; else hi = mid;
   }
   const int b = lo;
-  const int pos = a.first_pos[b] + (row - a.cu_rows[b]);
-  const int phys = a.block_ids[a.row_off[b] + pos / 16];
-  const int slot = pos % 16;
+  const int first = a.first_pos[b];
+  const int n_new = a.cu_rows[b + 1] - a.cu_rows[b];
+  const int blk = first / 16 + (wb - a.cu_wblk[b]);          // logical block
+  const int t_lo = max(first, blk * 16), t_hi = min(first + n_new, blk * 16 + 16);
+  const int s_lo = t_lo - blk * 16, s_hi = t_hi - blk * 16;  // slots [s_lo, s_hi) of the block are new
+  const int64_t row_lo = static_cast<int64_t>(a.cu_rows[b]) + (t_lo - first);   // source row of slot s_lo
   const int D = a.head_dim;
-  const int pieces_per_head = D / 8;
-  const int n_pieces = a.n_kv_heads * pieces_per_head;
-  for (int t = threadIdx.x; t < n_pieces; t += blockDim.x) {
-    const int h = t / pieces_per_head;
-    const int c = t - h * pieces_per_head;
-    const int64_t src = (static_cast<int64_t>(row) * a.n_kv_heads + h) * D + c * 8;
-    const int64_t tile_k = (static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 * D;
-    const int64_t tile_v = tile_k + 16 * D;
-    *reinterpret_cast<u32x4*>(a.pool + tile_k + slot * D + c * 8) = *reinterpret_cast<const u32x4*>(a.k + src);
-    const u32x4 vv = *reinterpret_cast<const u32x4*>(a.v + src);
-    const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint16_t x = static_cast<uint16_t>(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xffffu);
-      a.pool[tile_v + static_cast<int64_t>(c * 8 + e) * 16 + slot] = x;
+  const int pieces = D / 8;
+  const int phys = a.block_ids[a.row_off[b] + blk];
+  uint16_t* tile_k = a.pool + (static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 * D;
+  uint16_t* tile_v = tile_k + 16 * D;
+
+  for (int t = threadIdx.x; t < 16 * pieces; t += blockDim.x) {
+    const int slot = t / pieces, c = t - slot * pieces;
+    if (slot >= s_lo && slot < s_hi) {
+      const int64_t src = ((row_lo + (slot - s_lo)) * a.n_kv_heads + h) * D + c * 8;
+      *reinterpret_cast<u32x4*>(tile_k + slot * D + c * 8) = *reinterpret_cast<const u32x4*>(a.k + src);
+      *reinterpret_cast<u32x4*>(&s_v[slot][c * 8]) = *reinterpret_cast<const u32x4*>(a.v + src);
     }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < D * 2; t += blockDim.x) {
+    const int e = t >> 1, half = t & 1;                       // head-dim element, slots 8*half .. 8*half+7
+    const int lo8 = max(s_lo, 8 * half), hi8 = min(s_hi, 8 * half + 8);
+    if (lo8 >= hi8) continue;
+    u32x4* dst = reinterpret_cast<u32x4*>(tile_v + e * 16 + 8 * half);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (hi8 - lo8 < 8) {
+      const u32x4 old = *dst;
+      w[0] = old.x, w[1] = old.y, w[2] = old.z, w[3] = old.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int slot = 8 * half + j;
+      if (slot >= lo8 && slot < hi8) {
+        const uint32_t x = s_v[slot][e];
+        w[j >> 1] = (j & 1) ? (w[j >> 1] & 0x0000ffffu) | (x << 16) : (w[j >> 1] & 0xffff0000u) | x;
+      }
+    }
+    *dst = u32x4{w[0], w[1], w[2], w[3]};
   }
 }
 
@@ -97,8 +122,10 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, uint
 }  // namespace
 
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream) {
-  if (a.n_rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kv_write_kernel, dim3(static_cast<unsigned>(a.n_rows)), dim3(256), 0, stream, a);
+  if (a.n_rows <= 0 || a.n_wblk <= 0) return hipSuccess;
+  if (a.head_dim > 128) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(a.n_wblk) * static_cast<unsigned>(a.n_kv_heads));
+  hipLaunchKernelGGL(kv_write_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
