@@ -142,6 +142,14 @@ def main():
     t1 = time.perf_counter()
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
+    kernel_name = {0: "decode_splitk_kernel", 2: "append_attn_kernel", 4: "kv_move_kernel"}[dominant]
+    if kind == "append":
+        # tiles of at most 32 query rows per kv head run in the kernel that splits the keys over its waves
+        narrow_us, narrow_n = ctx.timing_read(7)
+        if narrow_n > 0 and (n_launch == 0 or narrow_us > kernel_us):
+            other_us, kernel_us, n_launch, kernel_name = kernel_us, narrow_us, narrow_n, "narrow_attn_kernel"
+        else:
+            other_us = narrow_us
     aux_us = ctx.timing_read({"decode": 1, "append": 3, "pack": 5}[kind])[0]
     group_us = ctx.timing_read(6)[0] if shared else 0.0
     ctx_combine_us = ctx.timing_read(1)[0]
@@ -173,8 +181,9 @@ def main():
         achieved = unit_bytes / (kernel_us * 1e-6) / 1e9
         roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                    "kernel": "append_attn_kernel", "kernel_avg_us": round(kernel_us, 2),
-                    "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2),
+                    "kernel": kernel_name, "kernel_avg_us": round(kernel_us, 2),
+                    "launches_timed": n_launch, "other_attn_kernel_avg_us": round(other_us, 2),
+                    "kv_write_avg_us": round(aux_us, 2),
                     "combine_avg_us": round(ctx_combine_us, 2), "flops_per_step": unit_flops}
     else:
         value = unit_flops / (ms_per_step * 1e-3) / 1e12
@@ -343,6 +352,7 @@ def run_placement(args, np, torch, hw, heddle):
 
 
 KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_attn_kernel": "append_kernels.hip",
+                  "narrow_attn_kernel": "narrow_kernels.hip",
                   "kv_move_kernel": "misc_kernels.hip"}
 
 

@@ -19,6 +19,7 @@ SOURCES = [
     "api.hip",
     "decode_kernels.hip",
     "append_kernels.hip",
+    "narrow_kernels.hip",
     "misc_kernels.hip",
 ]
 

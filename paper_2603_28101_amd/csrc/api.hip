@@ -16,7 +16,8 @@ using namespace heddle;
 namespace {
 
 constexpr int kStagingSlots = 8;
-constexpr int kTimedKernels = 7;       // split-K decode, combine, append, kv write, pack, unpack, shared prefix
+constexpr int kTimedKernels = 8;       // split-K decode, combine, append, kv write, pack, unpack, shared prefix,
+                                       // narrow append
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
 
 struct StagingSlot {
@@ -746,10 +747,17 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   }
   std::memcpy(h_len, args->ctx_len_host, sizeof(int32_t) * B);
   std::memcpy(h_cu, args->cu_chunk_host, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
+  // items of tiles with few rows go to the kernel that splits the keys over its waves; both lists
+  // keep the planner's longest-first order: [0, n_wide) wide, [n_wide, n_items) narrow
+  const int32_t narrow_rows = narrow_tile_rows(G);
+  size_t n_wide = 0;
+  for (const AppendItem& it : sp.items)
+    if (ctx->tiles[static_cast<size_t>(it.tile)].rows > narrow_rows) ++n_wide;
+  size_t next_wide = 0, next_narrow = n_wide;
   for (size_t i = 0; i < n_items; ++i) {
     const AppendItem& it = sp.items[i];
     const AppendTile& tl = ctx->tiles[static_cast<size_t>(it.tile)];
-    AppendItemRec& r = h_items[i];
+    AppendItemRec& r = h_items[tl.rows > narrow_rows ? next_wide++ : next_narrow++];
     r.b = tl.b;
     r.row0 = tl.row0;
     r.rows_n = tl.rows;
@@ -809,14 +817,20 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   al.q = static_cast<const uint16_t*>(args->q);
   al.out = static_cast<uint16_t*>(args->out);
   al.lse = args->lse;
-  al.n_items = static_cast<int32_t>(n_items);
+  al.n_items = static_cast<int32_t>(n_wide);
   al.n_q_heads = ctx->cfg.n_q_heads;
   al.n_kv_heads = ctx->cfg.n_kv_heads;
   al.head_dim = ctx->cfg.head_dim;
   al.scale_log2 = ctx->scale * 1.4426950408889634f;
-  {
+  if (n_wide > 0) {
     TimedScope t(ctx, 2, stream);
     HEDDLE_HIP(launch_append_attn(al, stream));
+  }
+  if (n_items > n_wide) {
+    al.items += n_wide;
+    al.n_items = static_cast<int32_t>(n_items - n_wide);
+    TimedScope t(ctx, 7, stream);
+    HEDDLE_HIP(launch_narrow_attn(al, stream));
   }
   if (any_split) {          // merge the parts of every row of a split tile; rows of other tiles are final
     DecodeLaunch dl{};

@@ -125,6 +125,10 @@ hipError_t launch_group_attn(const GroupLaunch& a, hipStream_t stream);
 bool append_shape_supported(int32_t group, int32_t head_dim);
 int32_t append_tile_rows(int32_t group);   // chunk rows per workgroup tile
 hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream);
+// Same arguments for items whose tile has at most narrow_tile_rows(G) chunk rows (32 query rows
+// per kv head): the four waves split the keys instead of the rows, nothing is staged in LDS.
+int32_t narrow_tile_rows(int32_t group);
+hipError_t launch_narrow_attn(const AppendLaunch& a, hipStream_t stream);
 
 // Copies n whole blocks pool[ids[i]] -> staging[i] (pack) or staging[i] -> pool[ids[i]] (unpack);
 // ids is a device array, block_bytes a multiple of 4096.
