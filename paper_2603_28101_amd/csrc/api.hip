@@ -749,10 +749,21 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   std::memcpy(h_cu, args->cu_chunk_host, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
   // items of tiles with few rows go to the kernel that splits the keys over its waves; both lists
   // keep the planner's longest-first order: [0, n_wide) wide, [n_wide, n_items) narrow
-  const int32_t narrow_rows = narrow_tile_rows(G);
+  // -- unless they are the smaller part of the batch: a few short-row tiles next to a large append
+  // would make a second launch that runs alone on a handful of compute units, while inside the
+  // large launch they cost next to nothing
+  int32_t narrow_rows = narrow_tile_rows(G);
   size_t n_wide = 0;
-  for (const AppendItem& it : sp.items)
-    if (ctx->tiles[static_cast<size_t>(it.tile)].rows > narrow_rows) ++n_wide;
+  int64_t steps_wide = 0, steps_narrow = 0;
+  for (const AppendItem& it : sp.items) {
+    const bool wide = ctx->tiles[static_cast<size_t>(it.tile)].rows > narrow_rows;
+    (wide ? steps_wide : steps_narrow) += it.step_end - it.step_begin;
+    n_wide += wide ? 1 : 0;
+  }
+  if (steps_narrow < steps_wide) {
+    narrow_rows = 0;
+    n_wide = n_items;
+  }
   size_t next_wide = 0, next_narrow = n_wide;
   for (size_t i = 0; i < n_items; ++i) {
     const AppendItem& it = sp.items[i];

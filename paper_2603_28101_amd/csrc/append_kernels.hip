@@ -158,28 +158,30 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
     for (int x = 0; x < kChunkBlocks; ++x) ids[x] = ctable[min(kChunkBlocks * c + x, n_blocks_needed - 1)];
   };
 
+  // byte offsets of this thread's pieces inside a (block, kv head) pair of tiles: with the pair's
+  // address in scalar registers a load needs no vector address arithmetic
+  const uint32_t k_piece = static_cast<uint32_t>(k_tok * D + k_slice * 8) * 2u;
+  const uint32_t v_piece = static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u;
+  const char* pool_h = reinterpret_cast<const char*>(a.pool + h * head_stride);
+
   u32x4 stage_k[kChunkBlocks], stage_v[kChunkBlocks];
   auto fetch = [&](int c) {               // uses the ids loaded by the preceding load_ids(c)
 #pragma unroll
     for (int x = 0; x < kChunkBlocks; ++x) {
+      // a block past the item's last one repeats that block (load_ids clamps): its keys are
+      // masked as beyond every row's position, and its V pieces are cleared below
       const int blk = kChunkBlocks * c + x;
-      if (blk < n_blocks_needed) {
-        const int phys = ids[x];
-        const uint16_t* t = a.pool + static_cast<int64_t>(phys) * block_stride + h * head_stride;
-        stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_tok * D + k_slice * 8);
-        u32x4 vv = *reinterpret_cast<const u32x4*>(t + kTileElems + v_row * kBlockTokens + v_half * 8);
-        const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist
-        if (nv < 8) {                                              // slots past the cache may hold NaN
-          vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
-          vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
-          vv.z &= (4 < nv ? 0x0000ffffu : 0u) | (5 < nv ? 0xffff0000u : 0u);
-          vv.w &= (6 < nv ? 0x0000ffffu : 0u) | (7 < nv ? 0xffff0000u : 0u);
-        }
-        stage_v[x] = vv;
-      } else {
-        stage_k[x] = u32x4{0u, 0u, 0u, 0u};
-        stage_v[x] = u32x4{0u, 0u, 0u, 0u};
+      const char* t = pool_h + static_cast<int64_t>(ids[x]) * (block_stride * 2);
+      stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_piece);
+      u32x4 vv = *reinterpret_cast<const u32x4*>(t + v_piece);
+      if (kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
+        const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
+        vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
+        vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
+        vv.z &= (4 < nv ? 0x0000ffffu : 0u) | (5 < nv ? 0xffff0000u : 0u);
+        vv.w &= (6 < nv ? 0x0000ffffu : 0u) | (7 < nv ? 0xffff0000u : 0u);
       }
+      stage_v[x] = vv;
     }
   };
   auto commit = [&](int st) {
