@@ -143,6 +143,9 @@ def main():
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     kernel_name = {0: "decode_splitk_kernel", 2: "append_attn_kernel", 4: "kv_move_kernel"}[dominant]
+    if kind == "decode" and n_launch == 0:
+        # with 8 query heads per kv head the library runs decode in the matrix-core kernel for short-row tiles
+        (kernel_us, n_launch), kernel_name = ctx.timing_read(7), "narrow_attn_kernel"
     if kind == "append":
         # tiles of at most 32 query rows per kv head run in the kernel that splits the keys over its waves
         narrow_us, narrow_n = ctx.timing_read(7)
@@ -170,7 +173,7 @@ def main():
         achieved = (private_bytes if shared else unit_bytes) / (kernel_us * 1e-6) / 1e9
         roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                    "kernel": "decode_splitk_kernel", "kernel_avg_us": round(kernel_us, 2),
+                    "kernel": kernel_name, "kernel_avg_us": round(kernel_us, 2),
                     "launches_timed": n_launch, "combine_avg_us": round(aux_us, 2)}
         if shared:
             roofline["kernel_bytes"] = private_bytes

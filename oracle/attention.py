@@ -167,7 +167,7 @@ def write_kv(pool_bits, row_off, block_ids, positions, b: int, k_bits, v_bits):
 
 
 def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_bits,
-           n_kv_heads: int, scale=None, rows=None, with_spread=False):
+           n_kv_heads: int, scale=None, rows=None, with_spread=False, centered=False):
     """Append a chunk per trajectory: first store the chunk's K/V rows at
     positions L_b .. L_b + C_b - 1 (pool_bits is modified in place), then each
     chunk row attends causally: row i of trajectory b sees L_b + i + 1 keys.
@@ -203,7 +203,7 @@ def append(pool_bits, row_off, block_ids, ctx_lens, cu_chunk, q_bits, k_bits, v_
             for j in range(n_q):
                 out[r, j], lse[r, j], w = attend(qr[j], K[j // G][:n_keys], V[j // G][:n_keys], s)
                 if with_spread:
-                    spread[r, j] = weight_spread(w, V[j // G][:n_keys], out[r, j], centered=False)
+                    spread[r, j] = weight_spread(w, V[j // G][:n_keys], out[r, j], centered)
     return (out, lse, spread) if with_spread else (out, lse)
 
 

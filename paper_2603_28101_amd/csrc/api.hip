@@ -614,8 +614,26 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * n_items);
   int32_t* h_first = w + 8 * n_items + 2 * static_cast<size_t>(B);
   int32_t* h_cu = h_first + B;
+  // With 8 query heads per kv head the packed-dot kernel is bound by its arithmetic; the
+  // matrix-core kernel for short-row tiles, fed the same plan as an append of one token per
+  // trajectory, is not.  It cuts keys at multiples of 64, so every item must start there.
+  bool on_matrix_cores = Hq / ctx->cfg.n_kv_heads == 8 && D == 128;
+  for (size_t i = 0; i < n_items && on_matrix_cores; ++i)
+    on_matrix_cores = ctx->items[i].blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
   for (size_t i = 0; i < n_items; ++i) {
     const DecodeItem& it = ctx->items[i];
+    if (on_matrix_cores) {
+      AppendItemRec& r = reinterpret_cast<AppendItemRec*>(w)[i];
+      r.b = it.b;
+      r.row0 = 0;
+      r.rows_n = 1;
+      r.key_end = std::min(args->len_host[it.b], it.blk_end * HEDDLE_BLOCK_TOKENS);
+      r.step_begin = it.blk_begin / (kAppendStepKeys / HEDDLE_BLOCK_TOKENS);
+      r.slot0 = ctx->part_off[it.b] + it.s;
+      r.nsplit = ctx->nsplit[it.b];
+      r.pad = 0;
+      continue;
+    }
     DecodeItemRec& r = h_items[i];
     r.b = it.b;
     r.slot = ctx->part_off[it.b] + it.s;
@@ -673,7 +691,27 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   dl.n_kv_heads = ctx->cfg.n_kv_heads;
   dl.head_dim = D;
   dl.scale_log2 = ctx->scale * 1.4426950408889634f;
-  {
+  if (on_matrix_cores) {
+    AppendLaunch al{};                         // the step seen as an append: L = len - 1, one new row each
+    al.pool = dl.pool;
+    al.row_off = args->row_off;
+    al.block_ids = args->block_ids;
+    al.ctx_len = d + (h_first - w);
+    al.cu_chunk = d + (h_cu - w);
+    al.items = reinterpret_cast<const AppendItemRec*>(d);
+    al.q = dl.q;
+    al.out = dl.out;
+    al.lse = dl.lse;
+    al.part_acc = dl.part_acc;
+    al.part_ml = dl.part_ml;
+    al.n_items = dl.n_items;
+    al.n_q_heads = Hq;
+    al.n_kv_heads = dl.n_kv_heads;
+    al.head_dim = D;
+    al.scale_log2 = dl.scale_log2;
+    TimedScope t(ctx, 7, stream);
+    HEDDLE_HIP(launch_narrow_attn(al, stream));
+  } else {
     TimedScope t(ctx, 0, stream);
     HEDDLE_HIP(launch_decode_splitk(dl, stream));
   }

@@ -105,6 +105,9 @@ struct GroupItemRec {
   int32_t pad[2];
 };
 
+static_assert(sizeof(DecodeItemRec) == 32 && sizeof(AppendItemRec) == 32 && sizeof(GroupItemRec) == 32,
+              "work item records are 32 bytes: the plan image reserves 8 words for each");
+
 // Arguments of the shared-prefix pass of a decode step: same matrix-core kernel as append, no
 // causal edge, and the result is a split-K partial per (member, query head) that the combine
 // kernel merges with the partials of the member's private blocks.

@@ -64,11 +64,11 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   constexpr int RS = kRows / G;                      // chunk rows per workgroup tile
   constexpr int kTileElems = kBlockTokens * D;
 
-  // merge buffer: [wave][mt][j][lane] accumulators, then [wave][2][lane] (max, sum).  During the
+  // merge buffer: [wave][mt][j][lane] accumulators, then [wave][3][lane] (max, rounded sum, sum).  During the
   // key loop the first 8 KB of a wave's accumulator area hold its K tile: key row t is 256 B,
   // its 16-byte piece c stored at slot c ^ (t & 15).
   __shared__ __attribute__((aligned(16))) float s_o[4][NMT][16][64];
-  __shared__ float s_ml[4][2][64];
+  __shared__ float s_ml[4][3][64];
 
   const int item = blockIdx.x / a.n_kv_heads;
   const int h = blockIdx.x - item * a.n_kv_heads;
@@ -103,7 +103,9 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) o[mt][j] = 0.0f;
-  float m_ref = -INFINITY, l_sum = 0.0f;
+  // l_sum: sum of the weights as they enter P.V (rounded to bf16), the output's denominator, so
+  // that the weights stay normalised; l_exact: unrounded, for the log-sum-exp
+  float m_ref = -INFINITY, l_sum = 0.0f, l_exact = 0.0f;
 
   const int64_t head_stride = 2 * kTileElems;
   const int64_t block_stride = static_cast<int64_t>(a.n_kv_heads) * head_stride;
@@ -202,6 +204,7 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
       const float m_new = fmaxf(m_ref, mx);
       const float shrink = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
       l_sum *= shrink;
+      l_exact *= shrink;
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       p[j] = __builtin_amdgcn_exp2f(fmaf(s[j], a.scale_log2, neg_m));
-      l_sum += p[j];
+      l_exact += p[j];
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -223,6 +226,10 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
       w.y = pack_bf16(p[8 * u + 2], p[8 * u + 3]);
       w.z = pack_bf16(p[8 * u + 4], p[8 * u + 5]);
       w.w = pack_bf16(p[8 * u + 6], p[8 * u + 7]);
+      l_sum += (__builtin_bit_cast(float, w.x << 16) + __builtin_bit_cast(float, w.x & 0xffff0000u)) +
+               (__builtin_bit_cast(float, w.y << 16) + __builtin_bit_cast(float, w.y & 0xffff0000u)) +
+               (__builtin_bit_cast(float, w.z << 16) + __builtin_bit_cast(float, w.z & 0xffff0000u)) +
+               (__builtin_bit_cast(float, w.w << 16) + __builtin_bit_cast(float, w.w & 0xffff0000u));
       const bf16x8 pb = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt)
@@ -248,12 +255,14 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   // ---- merge the four waves: wave w reduces head-dim rows 32 w .. 32 w + 31 of every query row
   wave_lds_fence();
   l_sum += __shfl_xor(l_sum, 32, 64);
+  l_exact += __shfl_xor(l_exact, 32, 64);
 #pragma unroll
   for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
     for (int j = 0; j < 16; ++j) s_o[wave][mt][j][lane] = o[mt][j];
   s_ml[wave][0][lane] = m_ref;
   s_ml[wave][1][lane] = l_sum;
+  s_ml[wave][2][lane] = l_exact;
   __syncthreads();
   float mw[4], M = -INFINITY;
 #pragma unroll
@@ -261,13 +270,14 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
     mw[w] = s_ml[w][0][lane];
     M = fmaxf(M, mw[w]);
   }
-  float l_all = 0.0f, acc[16];
+  float l_all = 0.0f, l_all_exact = 0.0f, acc[16];
 #pragma unroll
   for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
     const float f = mw[w] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(mw[w] - M);
     l_all = fmaf(f, s_ml[w][1][lane], l_all);
+    l_all_exact = fmaf(f, s_ml[w][2][lane], l_all_exact);
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = fmaf(f, s_o[w][wave][j][lane], acc[j]);
   }
@@ -280,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
     for (int jq = 0; jq < 4; ++jq)
       *reinterpret_cast<float4*>(ap + mt * 32 + 8 * jq + 4 * hi) =
           float4{acc[4 * jq + 0], acc[4 * jq + 1], acc[4 * jq + 2], acc[4 * jq + 3]};
-    if (wave == 0 && hi == 0) *reinterpret_cast<float4*>(a.part_ml + slot * 4) = float4{M, l_all, l_all, 0.0f};
+    if (wave == 0 && hi == 0) *reinterpret_cast<float4*>(a.part_ml + slot * 4) = float4{M, l_all, l_all_exact, 0.0f};
   } else {
     const float inv = 1.0f / l_all;
     uint16_t* op = a.out + (q_row * a.n_q_heads + head) * D;
@@ -292,7 +302,7 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
       *reinterpret_cast<u32x2*>(op + mt * 32 + 8 * jq + 4 * hi) = w;
     }
     if (a.lse != nullptr && wave == 0 && hi == 0)
-      a.lse[q_row * a.n_q_heads + head] = (M + __builtin_log2f(l_all)) * 0.6931471805599453f;
+      a.lse[q_row * a.n_q_heads + head] = (M + __builtin_log2f(l_all_exact)) * 0.6931471805599453f;
   }
 }
 

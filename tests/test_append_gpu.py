@@ -18,9 +18,11 @@ def small(seed, L, C, n_q=8, n_kv=2, d=128, **kw):
 
 
 def oracle_append(c, rows=None):
+    # the 128-row kernel divides by the unrounded weight sum, the kernel for short-row tiles by the
+    # sum of the rounded weights; a batch may use both, so the bound is the one for either
     pool = c["pool"].copy()
     out, lse, spread = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"], c["k_new"],
-                                 c["v_new"], c["n_kv_heads"], rows=rows, with_spread=True)
+                                 c["v_new"], c["n_kv_heads"], rows=rows, with_spread=True, centered=None)
     return pool, out, lse, spread
 
 
