@@ -165,7 +165,8 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   const char* pool_h = reinterpret_cast<const char*>(a.pool + h * head_stride);
 
   u32x4 stage_k[kChunkBlocks], stage_v[kChunkBlocks];
-  auto fetch = [&](int c) {               // uses the ids loaded by the preceding load_ids(c)
+  // may_pass_end: the chunk can hold slots past the cache (only the item's last chunk can)
+  auto fetch = [&](int c, auto may_pass_end) {   // uses the ids loaded by the preceding load_ids(c)
 #pragma unroll
     for (int x = 0; x < kChunkBlocks; ++x) {
       // a block past the item's last one repeats that block (load_ids clamps): its keys are
@@ -174,7 +175,8 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
       const char* t = pool_h + static_cast<int64_t>(ids[x]) * (block_stride * 2);
       stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_piece);
       u32x4 vv = *reinterpret_cast<const u32x4*>(t + v_piece);
-      if (kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
+      if (decltype(may_pass_end)::value &&
+          kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
         const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
         vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
         vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
@@ -196,16 +198,25 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   };
 
   load_ids(0);
-  fetch(0);
+  fetch(0, std::true_type{});
   load_ids(1);
   commit(0);
-  if (n_chunks > 1) fetch(1);
+  if (n_chunks > 1) fetch(1, std::true_type{});
   load_ids(2);
-  for (int c = 0; c < n_chunks; ++c) {
+  // One 64-key step.  kInterior: the step lies wholly before the causal edge of every row and at
+  // least three steps before the item's end, so it needs no mask and no test around its staging
+  // (the chunk it fetches, two steps ahead, is not the last one and has no slot past the cache):
+  // its body up to the rescale test is one straight run of code, which lets the LDS writes of the
+  // next stage, the global loads of the one after, the QK^T MFMAs and the row maximum be
+  // interleaved (a wave overlaps its own matrix and vector work well; two waves of a SIMD hardly
+  // overlap each other's).
+  auto step = [&](int c, auto interior) {
+    constexpr bool kInterior = decltype(interior)::value;
     const int st = c & 1;
     __syncthreads();                       // stage st is complete; nobody reads stage st^1 any more
-    if (c + 1 < n_chunks) commit(st ^ 1);
-    if (c + 2 < n_chunks) fetch(c + 2);    // global loads fly during the math below
+    if (kInterior || c + 1 < n_chunks) commit(st ^ 1);
+    if (kInterior) fetch(c + 2, std::false_type{});     // global loads fly during the math below
+    else if (c + 2 < n_chunks) fetch(c + 2, std::true_type{});
     load_ids(c + 3);                       // clamped to the tile's last block
 
     const int t0 = c * kChunkTokens;
@@ -226,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
     }
 
     // register j of tile u is key t0 + 32u + 8*(j/4) + 4*hi + j%4 of this lane's row
-    if (t0 + kChunkTokens - 1 > edge) {              // chunk reaches the causal edge of some row
+    if (!kInterior && t0 + kChunkTokens - 1 > edge) {   // chunk reaches the causal edge of some row
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -286,7 +297,13 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[mt], 0, 0, 0);
       }
     }
-  }
+  };
+
+  // steps [0, n_interior) are interior; the last three steps and those that reach the edge are not
+  const int n_interior = max(0, min(n_chunks - 3, (edge + 1) / kChunkTokens));
+  int c = 0;
+  for (; c < n_interior; ++c) step(c, std::true_type{});
+  for (; c < n_chunks; ++c) step(c, std::false_type{});
 
   // ---- normalise and store: register j of tile mt is head-dim element mt*32 + 8*(j/4) + 4*hi + j%4
   l_sum += __shfl_xor(l_sum, 32, 64);
