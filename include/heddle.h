@@ -35,8 +35,11 @@
  * Conventions.  Every function returns HEDDLE_OK (0) or a negative code; no
  * exceptions, no abort, nothing printed.  Arguments are validated before any
  * device work is enqueued, so a failing call has no device side effect.
- * Attention calls are asynchronous on the HIP stream passed in and never
- * synchronise it; host arrays are consumed before the call returns.  A context
+ * Attention calls are asynchronous on the HIP stream passed in and do not
+ * synchronise it, with one exception: when the library's scratch (plan image,
+ * split-K partials) has to grow - on the first call, or on a call larger than
+ * any before - the device is synchronised once and the scratch reallocated.
+ * Host arrays are consumed before the call returns.  A context
  * is not thread-safe and its attention calls must be issued on one stream at a
  * time (they share the context's scratch).
  */
