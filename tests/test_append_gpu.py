@@ -224,3 +224,50 @@ def test_split_parts_meet_the_causal_edge():
     out, lse = dc.append()
     assert_close(out, ref, "parts at the causal edge", spread)
     assert_lse_close(lse, ref_lse, "parts at the causal edge lse")
+
+
+def _sampled_rows(c, trajectories):
+    cu = c["cu_chunk"]
+    rows = []
+    for b in trajectories:
+        C = int(cu[b + 1] - cu[b])
+        rows += [int(cu[b]) + r for r in sorted({0, 1, C // 2, C - 1}) if 0 <= r < C]
+    return sorted(set(rows))
+
+
+@pytest.mark.parametrize("cfg", [7, 8])
+def test_full_size_small_batch_workloads_sampled(cfg):
+    """The verify-4-tokens and straggler-append workloads at full size, in the configuration the
+    benchmark times: sampled rows against the oracle, and the pool after the call bit for bit."""
+    c = hw.make_workload(cfg, 0, threads=16)
+    dc = DeviceCase(c)
+    sp = dc.ctx.plan_append_split(c["lens"], c["cu_chunk"])
+    assert sp["tile_nsplit"].max() > 1                      # the long ones are cut
+    out, lse = dc.append()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    order = np.argsort(c["lens"])
+    picks = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])})
+    rows = _sampled_rows(c, picks)
+    print(f"workload {cfg}: {len(rows)} sampled rows of trajectories {picks}", flush=True)
+    pool, ref, ref_lse, spread = oracle_append(c, rows=rows)
+    assert_close(out[rows], ref[rows], f"workload {cfg}", spread[rows])
+    assert_lse_close(lse[rows], ref_lse[rows], f"workload {cfg} lse")
+    assert np.array_equal(dc.pool_bits(), pool)
+
+
+def test_append_up_to_the_maximum_context():
+    """Chunks that end exactly at the largest context the library accepts, one through the
+    128-row kernel (40 rows), one through the short-row kernel (3 rows), both cut into parts."""
+    top = 131072
+    c = small(34, [top - 40, top - 3, 5], [40, 3, 2], 8, 2, 128)
+    dc = DeviceCase(c)
+    out, lse = dc.append()
+    rows = _sampled_rows(c, [0, 1, 2])
+    pool, ref, ref_lse, spread = oracle_append(c, rows=rows)
+    assert_close(out[rows], ref[rows], "maximum context append", spread[rows])
+    assert_lse_close(lse[rows], ref_lse[rows], "maximum context append lse")
+    assert np.array_equal(dc.pool_bits(), pool)
+    import paper_2603_28101_amd as heddle
+    with pytest.raises(heddle.HeddleError):                 # one token more is refused before any device work
+        over = small(35, [top - 2], [3], 8, 2, 128)
+        DeviceCase(over).append()
