@@ -67,11 +67,14 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   constexpr int kTileElems = kBlockTokens * D;
   constexpr int kStageK = kChunkTokens * D;            // elements of K per LDS stage
   constexpr int kStageV = kChunkBlocks * kTileElems;   // elements of V per LDS stage
+  constexpr int kVPlane = D * 8;                       // elements of one 8-key plane of a V block
 
   // Two stages (double buffer).  K rows are 256 B = 16 slots of 16 B; slot c of key row t is
   // stored at slot c ^ (t & 15), so that the 32 lanes reading the same d-slice of 32
-  // different keys spread over all banks.  V rows are 32 B with their four 4-key groups in
-  // the order {0-3, 8-11, 4-7, 12-15}.
+  // different keys spread over all banks.  A V block is two planes of [d][8 keys]: plane 0
+  // holds keys {0-3, 8-11}, plane 1 keys {4-7, 12-15}, so that the 16 lanes an LDS read serves
+  // per cycle (consecutive head-dim rows of one plane) fall into 16 different bank groups;
+  // with [d][16 keys] rows every other row of a half collided.
   __shared__ __attribute__((aligned(16))) uint16_t s_k[2][kStageK];
   __shared__ __attribute__((aligned(16))) uint16_t s_v[2][kStageV];
 
@@ -191,9 +194,9 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
     for (int x = 0; x < kChunkBlocks; ++x) {
       const int row = x * kBlockTokens + k_tok;
       *reinterpret_cast<u32x4*>(&s_k[st][row * D + ((k_slice ^ k_tok) * 8)]) = stage_k[x];
-      uint16_t* vrow = &s_v[st][x * kTileElems + v_row * kBlockTokens];
-      *reinterpret_cast<u32x2*>(vrow + v_half * 4) = u32x2{stage_v[x].x, stage_v[x].y};        // keys 8h+0..3
-      *reinterpret_cast<u32x2*>(vrow + 8 + v_half * 4) = u32x2{stage_v[x].z, stage_v[x].w};    // keys 8h+4..7
+      uint16_t* vrow = &s_v[st][x * kTileElems + v_row * 8 + v_half * 4];
+      *reinterpret_cast<u32x2*>(vrow) = u32x2{stage_v[x].x, stage_v[x].y};                 // keys 8h+0..3 -> plane 0
+      *reinterpret_cast<u32x2*>(vrow + kVPlane) = u32x2{stage_v[x].z, stage_v[x].w};       // keys 8h+4..7 -> plane 1
     }
   };
 
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt) {
         const bf16x8 va = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st][x * kTileElems + (mt * 32 + n) * kBlockTokens + hi * 8]));
+            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st][x * kTileElems + hi * kVPlane + (mt * 32 + n) * 8]));
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[mt], 0, 0, 0);
       }
     }
