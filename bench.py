@@ -253,7 +253,7 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case, w, np, kind)
+        result["cpu_baseline"] = cpu_baseline(case, w, np, kind, unit)
     print(json.dumps(result))
 
 
@@ -380,7 +380,7 @@ def recorded_traffic(w, kernel):
     return int(m.group(1))
 
 
-def cpu_baseline(case, w, np, kind):
+def cpu_baseline(case, w, np, kind, unit):
     """The oracle as it stands, timed on this host on a bounded sample."""
     from oracle import attention as oa
     try:
@@ -417,18 +417,23 @@ def cpu_baseline(case, w, np, kind):
     # rows (first, second, last two and every 97th of each trajectory), all heads, in one call
     pool = case["pool"].copy()
     L, cu = case["lens"], case["cu_chunk"]
-    rows, flops = [], 0
+    rows, flops, kv_bytes = [], 0, 0
     for b in range(len(L)):
         C = int(cu[b + 1] - cu[b])
         for r in sorted({0, 1, C - 2, C - 1} | set(range(0, C, 97))):
             if 0 <= r < C:
                 rows.append(int(cu[b]) + r)
                 flops += 4 * w.head_dim * w.n_q_heads * (int(L[b]) + r + 1)
+                kv_bytes += (int(L[b]) + r + 1) * 2 * w.n_kv_heads * w.head_dim * 2
     oa.append(pool, case["row_off"], case["block_ids"], L, cu, case["q"], case["k_new"], case["v_new"],
               w.n_kv_heads, rows=rows)
     dt = time.perf_counter() - t0
-    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": blas_threads, "kind": "oracle",
-            "sample": f"{len(rows)} sampled chunk rows of all {len(L)} trajectories, all heads "
+    if unit == "GB/s":      # the pass is priced in K/V bytes: bytes of the keys the sampled rows visit
+        value, what = round(kv_bytes / dt / 1e9, 4), f"{kv_bytes} bytes of visible K/V"
+    else:
+        value, what = round(flops / dt / 1e12, 6), f"{flops} flops"
+    return {"value": value, "unit": unit, "cores": blas_threads, "kind": "oracle",
+            "sample": f"{len(rows)} sampled chunk rows of all {len(L)} trajectories, all heads: {what} "
                       f"({dt:.1f} s, includes the oracle's KV write and gather)",
             "host_cpus": os.cpu_count(), "affinity": len(os.sched_getaffinity(0))}
 
