@@ -162,7 +162,8 @@ int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_
  *     steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
  *  3. a tile with n > 1 owns rows_n * n partial slots from part_base_t (assigned in
  *     tile order); row r, part k -> part_base_t + r*n + k.
- *  4. items (t, k) sorted by (-(step_end - step_begin), t, k).
+ *  4. items (t, k) sorted by (-(step_end - step_begin), b_t, step_begin, row0_t): equally
+ *     long parts of one trajectory's tiles over the same keys run side by side.
  * heddle_attn_append applies this rule itself; the function exposes it for checking. */
 typedef struct heddle_append_split_plan {
   int32_t  cap_tiles, cap_items;            /* in  */

@@ -245,7 +245,9 @@ def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_
          covers steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
       3. Tiles with n > 1 own rows_n * n partial slots from part_base_t on (bases assigned in
          tile order); row r of the tile, part k -> slot part_base_t + r*n + k.
-      4. items (t, k) sorted by (-(step_end - step_begin), t, k).
+      4. items (t, k) sorted by (-(step_end - step_begin), b_t, step_begin, row0_t): among equally
+         long items, those of one trajectory that cover the same keys (parts of its different
+         tiles) are neighbours, run at the same time and share the K/V they read in cache.
     Returns tile_nsplit[n_tiles], tile_part_base[n_tiles], n_slots, and item arrays
     item_tile, item_k, item_step_begin, item_step_end."""
     n_tiles = int(plan["n_tiles"])
@@ -271,11 +273,11 @@ def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_
         for k in range(nsplit[t]):
             lo = k * per_of[t]
             hi = S[t] if k == nsplit[t] - 1 else (k + 1) * per_of[t]
-            items.append((-(hi - lo), t, k, lo, hi))
+            items.append((-(hi - lo), int(plan["tile_b"][t]), lo, int(plan["tile_row0"][t]), t, k, hi))
     items.sort()
     i32 = lambda v: np.asarray(v, dtype=np.int32)
     return dict(
         tile_nsplit=i32(nsplit), tile_part_base=i32(part_base), n_slots=base, n_items=len(items),
-        item_tile=i32([it[1] for it in items]), item_k=i32([it[2] for it in items]),
-        item_step_begin=i32([it[3] for it in items]), item_step_end=i32([it[4] for it in items]),
+        item_tile=i32([it[4] for it in items]), item_k=i32([it[5] for it in items]),
+        item_step_begin=i32([it[2] for it in items]), item_step_end=i32([it[6] for it in items]),
     )

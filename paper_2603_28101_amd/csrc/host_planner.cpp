@@ -224,8 +224,16 @@ void split_append_tiles(const PlanParams& p, int32_t append_wg_per_cu, int32_t m
       out.items.push_back(it);
     }
   }
-  std::stable_sort(out.items.begin(), out.items.end(), [](const AppendItem& x, const AppendItem& y) {
-    return (x.step_end - x.step_begin) > (y.step_end - y.step_begin);
+  // longest first; among equals by (trajectory, first step, first row): parts of different tiles of
+  // one trajectory that cover the same keys become neighbours and share those keys in cache
+  std::sort(out.items.begin(), out.items.end(), [&tiles](const AppendItem& x, const AppendItem& y) {
+    const int32_t lx = x.step_end - x.step_begin, ly = y.step_end - y.step_begin;
+    if (lx != ly) return lx > ly;
+    const AppendTile& tx = tiles[static_cast<size_t>(x.tile)];
+    const AppendTile& ty = tiles[static_cast<size_t>(y.tile)];
+    if (tx.b != ty.b) return tx.b < ty.b;
+    if (x.step_begin != y.step_begin) return x.step_begin < y.step_begin;
+    return tx.row0 < ty.row0;
   });
 }
 
