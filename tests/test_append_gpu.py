@@ -196,7 +196,7 @@ def test_single_long_trajectory_short_chunk_is_split_and_exact():
     assert_lse_close(lse, ref_lse, "split append lse")
 
 
-@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (16, 2), (32, 8)])
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8)])
 def test_short_multi_token_decode(n_q, n_kv):
     """A verify step of speculative decoding: 2-8 new tokens on each of a few trajectories of very
     different lengths (ragged parts, L = 0 among them); default plan and one forced into many parts."""
