@@ -1,0 +1,175 @@
+"""A small rollout through every entry point in the order a worker would call them (paper
+Sec. 2.1: a trajectory alternates generation with tool calls and keeps its context; Sec. 4.2: a
+preempted trajectory keeps its cache; Sec. 7: the samples of a prompt share its tokens):
+
+  prompt prefill (append with L = 0) -> decode steps that store their own K/V row -> a tool-output
+  chunk (append) -> more decode -> one trajectory is packed, its blocks freed and handed to
+  another, later it is unpacked under new blocks -> decode with shared prompt blocks.
+
+The library's block manager hands out the blocks; the float64 oracle mirrors every call on its own
+copy of the pool, and outputs and the pool are compared after each call.  Needs the GPU."""
+import numpy as np
+import pytest
+
+import heddle_workloads as hw
+from oracle import attention as oa
+from oracle.kv_manager import KVManager
+from tests.gpu_util import (assert_close, assert_lse_close, bf16_to_host_bits, bits_to_f64, to_dev_bf16, to_dev_i32,
+                            torch_mod)
+
+pytestmark = pytest.mark.gpu
+
+N_Q, N_KV, D = 8, 2, 128
+N_BLOCKS = 400
+
+
+def bf16(rng, shape):
+    return hw.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+
+
+class Worker:
+    """Library context and oracle state side by side."""
+
+    def __init__(self, seed):
+        import paper_2603_28101_amd as heddle
+        torch = torch_mod()
+        self.rng = np.random.default_rng(seed)
+        pool = np.full((N_BLOCKS, N_KV, 2, 16 * D), 0x7FC0, dtype=np.uint16)       # everything starts as NaN
+        self.ref_pool = pool.copy()
+        self.pool = to_dev_bf16(pool)
+        self.ctx = heddle.Context(N_Q, N_KV, D, N_BLOCKS, kv_pool=self.pool, device=0)
+        self.ref_blocks = KVManager(N_BLOCKS)
+        self.tables = []          # per trajectory: list of physical blocks
+        self.lens = []            # tokens stored
+        self.torch = torch
+
+    # -- blocks: the library's manager and the oracle's must hand out the same ids
+    def grow(self, b, tokens):
+        need = -(-tokens // 16) - len(self.tables[b])
+        if need > 0:
+            got = self.ctx.kv_alloc(need)
+            code, ref = self.ref_blocks.alloc(need)
+            assert code == 0 and got.tolist() == ref
+            self.tables[b] += got.tolist()
+
+    def csr(self, order):
+        row_off = np.concatenate([[0], np.cumsum([len(self.tables[b]) for b in order])]).astype(np.int32)
+        ids = np.asarray([x for b in order for x in self.tables[b]], dtype=np.int32)
+        return row_off, ids
+
+    def check_pool(self, what):
+        got = bf16_to_host_bits(self.pool).reshape(self.ref_pool.shape)
+        assert np.array_equal(got, self.ref_pool), f"pool differs after {what}"
+
+    # -- calls
+    def append(self, order, chunk_lens, what):
+        rng, torch = self.rng, self.torch
+        for b, c in zip(order, chunk_lens):
+            self.grow(b, self.lens[b] + c)
+        row_off, ids = self.csr(order)
+        n_rows = int(sum(chunk_lens))
+        q, k, v = bf16(rng, (n_rows, N_Q, D)), bf16(rng, (n_rows, N_KV, D)), bf16(rng, (n_rows, N_KV, D))
+        L = np.asarray([self.lens[b] for b in order], dtype=np.int32)
+        cu = np.concatenate([[0], np.cumsum(chunk_lens)]).astype(np.int32)
+        out = torch.full((n_rows, N_Q, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((n_rows, N_Q), float("nan"), dtype=torch.float32, device="cuda")
+        self.ctx.attn_append(L, cu, row_off, to_dev_i32(row_off), to_dev_i32(ids), to_dev_bf16(q), to_dev_bf16(k),
+                             to_dev_bf16(v), out, lse)
+        torch.cuda.synchronize()
+        ref, ref_lse, spread = oa.append(self.ref_pool, row_off, ids, L, cu, q, k, v, N_KV, with_spread=True,
+                                         centered=None)
+        assert_close(bits_to_f64(bf16_to_host_bits(out)), ref, what, spread)
+        assert_lse_close(lse.cpu().numpy(), ref_lse, what)
+        for b, c in zip(order, chunk_lens):
+            self.lens[b] += c
+        self.check_pool(what)
+
+    def decode(self, order, what, shared=False):
+        rng, torch = self.rng, self.torch
+        for b in order:
+            self.grow(b, self.lens[b] + 1)
+        row_off, ids = self.csr(order)
+        B = len(order)
+        q, k, v = bf16(rng, (B, N_Q, D)), bf16(rng, (B, N_KV, D)), bf16(rng, (B, N_KV, D))
+        lens = np.asarray([self.lens[b] + 1 for b in order], dtype=np.int32)      # the new row included
+        out = torch.full((B, N_Q, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, N_Q), float("nan"), dtype=torch.float32, device="cuda")
+        args = (to_dev_i32(row_off), to_dev_i32(ids), to_dev_bf16(q), out, lse, to_dev_bf16(k), to_dev_bf16(v))
+        if shared:
+            plan = self.ctx.plan_decode_shared(lens, row_off, ids)
+            assert plan["n_groups"] >= 1, "the samples of a prompt were expected to share its blocks"
+            self.ctx.attn_decode_shared(lens, row_off, ids, *args)
+        else:
+            self.ctx.attn_decode(lens, row_off, *args)
+        torch.cuda.synchronize()
+        for i in range(B):
+            oa.write_kv(self.ref_pool, row_off, ids, [int(lens[i]) - 1], i, k[i:i + 1], v[i:i + 1])
+        ref, ref_lse, spread = oa.decode(self.ref_pool, row_off, ids, lens, q, N_KV, with_spread=True,
+                                         centered=None if shared else True)
+        assert_close(bits_to_f64(bf16_to_host_bits(out)), ref, what, spread)
+        assert_lse_close(lse.cpu().numpy(), ref_lse, what)
+        for b in order:
+            self.lens[b] += 1
+        self.check_pool(what)
+
+
+def test_rollout_of_six_trajectories():
+    torch = torch_mod()
+    w = Worker(2026)
+    # two prompts; samples 0-2 belong to the first, 3-5 to the second
+    prompts = [200, 75]
+    w.tables = [[] for _ in range(6)]
+    w.lens = [0] * 6
+
+    # 1. prefill the two prompts once each (trajectories 0 and 3)
+    w.append([0, 3], prompts, "prompt prefill")
+    # the other samples of a prompt start from its whole blocks (shared physically) and copy the
+    # partly filled last block into a block of their own
+    for leader, members in ((0, (1, 2)), (3, (4, 5))):
+        whole = w.lens[leader] // 16
+        for b in members:
+            w.tables[b] = list(w.tables[leader][:whole])
+            w.lens[b] = whole * 16
+    tail = [w.lens[0] - (w.lens[0] // 16) * 16, w.lens[3] - (w.lens[3] // 16) * 16]     # 8 and 11 tokens
+    # re-append those tail tokens for the members (in a real rollout: a copy; here fresh rows)
+    w.append([1, 2, 4, 5], [tail[0], tail[0], tail[1], tail[1]], "prompt tails of the other samples")
+    assert w.lens == [200, 200, 200, 75, 75, 75]
+
+    # 2. a few decode steps for everybody, shared-prefix path (12 and 4 whole prompt blocks)
+    for step in range(3):
+        w.decode([0, 1, 2, 3, 4, 5], f"shared decode step {step}", shared=True)
+    # 3. tool outputs of very different sizes for some, a verify-like 3-token chunk for one
+    w.append([1, 4, 5], [150, 33, 3], "tool outputs")
+    # 4. plain decode in a different batch order, twice
+    for step in range(2):
+        w.decode([5, 2, 0, 4], f"decode step {step}")
+
+    # 5. trajectory 1 is preempted: packed, its private blocks freed ...
+    b = 1
+    n_blk = -(-w.lens[b] // 16)
+    shared_blk = prompts[0] // 16                       # the prompt's whole blocks stay with samples 0 and 2
+    private = w.tables[b][shared_blk:n_blk]
+    staging = torch.empty((len(private), N_KV * 2 * 16 * D), dtype=torch.bfloat16, device="cuda")
+    w.ctx.kv_pack(np.asarray(private, dtype=np.int32), staging)
+    torch.cuda.synchronize()
+    row_off, ids = w.csr([b])
+    staged_ref = oa.pack(w.ref_pool, row_off, ids, 0, w.lens[b])[shared_blk:]
+    assert np.array_equal(bf16_to_host_bits(staging).reshape(staged_ref.shape), staged_ref)
+    w.ctx.kv_free(np.asarray(w.tables[b][shared_blk:], dtype=np.int32))
+    assert w.ref_blocks.free(w.tables[b][shared_blk:]) == 0
+    w.tables[b] = w.tables[b][:shared_blk]
+    # ... which the next tool output of trajectory 3 takes (most recently freed first)
+    w.append([3], [300], "tool output into recycled blocks")
+    # 6. trajectory 1 comes back under new blocks
+    got = w.ctx.kv_alloc(len(private))
+    code, ref_ids = w.ref_blocks.alloc(len(private))
+    assert code == 0 and got.tolist() == ref_ids
+    w.ctx.kv_unpack(got, staging)
+    torch.cuda.synchronize()
+    oa.unpack(w.ref_pool, got, staged_ref)
+    w.tables[b] += got.tolist()
+    w.check_pool("unpack")
+    # 7. everybody decodes again, shared path, then plain
+    w.decode([0, 1, 2, 3, 4, 5], "shared decode after resume", shared=True)
+    w.decode([0, 1, 2, 3, 4, 5], "decode after resume")
+    assert w.ctx.kv_num_free() == w.ref_blocks.num_free()
