@@ -39,7 +39,10 @@
  * synchronise it, with one exception: when the library's scratch (plan image,
  * split-K partials) has to grow - on the first call, or on a call larger than
  * any before - the device is synchronised once and the scratch reallocated.
- * Host arrays are consumed before the call returns.  A context
+ * Host arrays are consumed before the call returns.  Every attention call plans
+ * its work on the host from the lengths it is given and uploads that plan, so a
+ * call is not something to capture into a HIP graph and replay: a replay would
+ * run the plan of the captured lengths.  A context
  * is not thread-safe and its attention calls must be issued on one stream at a
  * time (they share the context's scratch).
  */
