@@ -271,3 +271,17 @@ def test_append_up_to_the_maximum_context():
     with pytest.raises(heddle.HeddleError):                 # one token more is refused before any device work
         over = small(35, [top - 2], [3], 8, 2, 128)
         DeviceCase(over).append()
+
+
+def test_softmax_scale_of_the_context_is_used():
+    """A scale other than 1/sqrt(d) in the 128-row kernel (chunks of 40 and 70 rows) and in the
+    short-row kernel (chunks of 3 and 5 rows)."""
+    for C in ([40, 70], [3, 5]):
+        c = small(36, [100, 3000], C, 8, 2, 128)
+        for scale in (0.03, 0.25):
+            pool = c["pool"].copy()
+            ref, ref_lse, spread = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"],
+                                             c["k_new"], c["v_new"], 2, scale=scale, with_spread=True, centered=None)
+            out, lse = DeviceCase(c, scale=scale).append()
+            assert_close(out, ref, f"append scale {scale}", spread)
+            assert_lse_close(lse, ref_lse, f"append scale {scale} lse")

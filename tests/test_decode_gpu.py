@@ -235,3 +235,16 @@ def test_dominant_logits_and_large_values():
     ref, ref_lse, spread = oracle_decode(c)
     assert_close(out, ref, "dominant logits", spread)
     assert np.abs(lse - ref_lse).max() < 1e-3 * np.maximum(1.0, np.abs(ref_lse)).max()
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (16, 2)])
+def test_softmax_scale_of_the_context_is_used(n_q, n_kv):
+    """A scale other than 1/sqrt(d), in the packed-dot kernel (G = 4) and in the matrix-core kernel
+    that runs decode at G = 8."""
+    c = small(21, [1, 40, 700, 5000], n_q, n_kv, 128)
+    for scale in (0.03, 0.25):
+        ref, ref_lse, spread = oa.decode(c["pool"], c["row_off"], c["block_ids"], c["lens"], c["q"], n_kv, scale=scale,
+                                         with_spread=True)
+        out, lse = DeviceCase(c, scale=scale).decode()
+        assert_close(out, ref, f"scale {scale}", spread)
+        assert_lse_close(lse, ref_lse, f"scale {scale} lse")
