@@ -142,20 +142,23 @@ def main():
     t1 = time.perf_counter()
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
+    timer_of_kernel = dominant
     kernel_name = {0: "decode_splitk_kernel", 2: "append_attn_kernel", 4: "kv_move_kernel"}[dominant]
     if kind == "decode" and n_launch == 0:
         # with 8 query heads per kv head the library runs decode in the matrix-core kernel for short-row tiles
-        (kernel_us, n_launch), kernel_name = ctx.timing_read(7), "narrow_attn_kernel"
+        (kernel_us, n_launch), kernel_name, timer_of_kernel = ctx.timing_read(7), "narrow_attn_kernel", 7
     if kind == "append":
         # tiles of at most 32 query rows per kv head run in the kernel that splits the keys over its waves
         narrow_us, narrow_n = ctx.timing_read(7)
         if narrow_n > 0 and (n_launch == 0 or narrow_us > kernel_us):
             other_us, kernel_us, n_launch, kernel_name = kernel_us, narrow_us, narrow_n, "narrow_attn_kernel"
+            timer_of_kernel = 7
         else:
             other_us = narrow_us
     aux_us = ctx.timing_read({"decode": 1, "append": 3, "pack": 5}[kind])[0]
     group_us = ctx.timing_read(6)[0] if shared else 0.0
     ctx_combine_us = ctx.timing_read(1)[0]
+    kernel_samples = ctx.timing_samples(timer_of_kernel)
     ctx.timing_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -219,6 +222,10 @@ def main():
     torch.cuda.synchronize()
 
     roofline["traffic"] = recorded_traffic(w, roofline["kernel"])
+    if kernel_samples.size:
+        # spread of the timed launches of that kernel (the roofline uses their mean)
+        p10, p50, p90 = np.percentile(kernel_samples.astype(np.float64), [10, 50, 90])
+        roofline["kernel_us_p10_p50_p90"] = [round(float(p10), 2), round(float(p50), 2), round(float(p90), 2)]
 
     extra = {}
     if kind == "decode" and shared:

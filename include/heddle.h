@@ -337,6 +337,11 @@ int heddle_simulate_group(int32_t n, const int32_t* lengths, int32_t n_prof, con
  * (short chunks; decode with 8 query heads per kv head). */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
 int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
+/* The recorded launches one by one: writes the durations (microseconds) of up to
+ * `cap` of them to us_out (HOST, in no particular order once more than 2048 were
+ * recorded and old ones overwritten) and the number held to *n_out; cap = 0
+ * only counts.  Synchronises the recorded events. */
+int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us_out, int64_t* n_out);
 
 /* Streams `bytes` bytes from `src` (DEVICE) through a plain coalesced read kernel
  * and writes one checksum word per workgroup to `sink` (DEVICE, >= 4096 uint32);

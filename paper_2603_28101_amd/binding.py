@@ -126,6 +126,7 @@ lib.heddle_interference_table.argtypes = [C.c_int32, f64p, f64p, C.c_int32, f64p
 lib.heddle_simulate_group.argtypes = [C.c_int32, i32p, C.c_int32, f64p, f64p, f64p]
 lib.heddle_timing_enable.argtypes = [vp, C.c_int32]
 lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+lib.heddle_timing_samples.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
 lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
@@ -133,7 +134,7 @@ lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
-           "heddle_timing_read", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
+           "heddle_timing_read", "heddle_timing_samples", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
            "heddle_interference_table", "heddle_simulate_group",
            "heddle_version"):
     getattr(lib, _f).restype = C.c_int
@@ -386,6 +387,15 @@ class Context:
         us, n = C.c_double(), C.c_int64()
         _check(lib.heddle_timing_read(self._h, which, C.byref(us), C.byref(n)), "heddle_timing_read")
         return us.value, n.value
+
+    def timing_samples(self, which: int) -> np.ndarray:
+        """Durations in microseconds of the recorded launches of one kernel (at most the last 2048)."""
+        n = C.c_int64()
+        _check(lib.heddle_timing_samples(self._h, which, 0, None, C.byref(n)), "heddle_timing_samples")
+        out = np.empty(min(n.value, 2048), dtype=np.float32)
+        _check(lib.heddle_timing_samples(self._h, which, out.shape[0], out.ctypes.data_as(C.POINTER(C.c_float)),
+                                         C.byref(n)), "heddle_timing_samples")
+        return out
 
 
 def stream_read(src, nbytes: int, sink, stream=None) -> None:

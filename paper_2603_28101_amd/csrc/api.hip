@@ -980,6 +980,26 @@ int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* 
   return HEDDLE_OK;
 }
 
+int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us_out, int64_t* n_out) {
+  if (ctx == nullptr || which < 0 || which >= kTimedKernels || n_out == nullptr || cap < 0 ||
+      (cap > 0 && us_out == nullptr))
+    return HEDDLE_E_INVAL;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  KernelTimer& t = ctx->timers[which];
+  const int64_t have = t.recorded < kEventPairs ? t.recorded : kEventPairs;
+  const int64_t n = have < cap ? have : cap;
+  for (int64_t i = 0; i < n; ++i) {
+    HEDDLE_HIP(hipEventSynchronize(t.stop[i]));
+    float ms = 0.f;
+    HEDDLE_HIP(hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+    us_out[i] = ms * 1000.0f;
+  }
+  *n_out = have;
+  return HEDDLE_OK;
+}
+
 int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream) {
   if (src == nullptr || sink == nullptr || bytes < 16) return HEDDLE_E_INVAL;
   HEDDLE_HIP(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)));

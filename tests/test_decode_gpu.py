@@ -248,3 +248,31 @@ def test_softmax_scale_of_the_context_is_used(n_q, n_kv):
         out, lse = DeviceCase(c, scale=scale).decode()
         assert_close(out, ref, f"scale {scale}", spread)
         assert_lse_close(lse, ref_lse, f"scale {scale} lse")
+
+
+def test_kernel_timers_count_and_time_the_launches():
+    """The measurement aids: with recording on every launch, three decode calls leave three
+    durations per launched kernel, the average is their mean, recording every 2nd launch keeps
+    two of three, and turning recording off leaves the results unchanged."""
+    c = small(31, [5000, 300, 17], 8, 2, 128)
+    ref, _, spread = oracle_decode(c)
+    dc = DeviceCase(c, n_cu=4, wg_per_cu=1, min_chunk_blk=16)      # the long trajectory is split: both kernels run
+    dc.ctx.timing_enable(1)
+    for _ in range(3):
+        out, _ = dc.decode()
+    assert_close(out, ref, "timed decode", spread)
+    for which in (0, 1):                       # split-K kernel, combine kernel
+        avg, n = dc.ctx.timing_read(which)
+        samples = dc.ctx.timing_samples(which)
+        assert n == 3 and samples.shape == (3,)
+        assert (samples > 0).all() and (samples < 1e5).all()
+        assert abs(avg - float(samples.astype(np.float64).mean())) <= 1e-3 * avg
+    assert dc.ctx.timing_read(2)[1] == 0 and dc.ctx.timing_samples(2).shape == (0,)      # no append was launched
+    dc.ctx.timing_enable(2)
+    for _ in range(3):
+        dc.decode()
+    assert dc.ctx.timing_read(0)[1] == 2
+    dc.ctx.timing_enable(0)
+    out, _ = dc.decode()
+    assert dc.ctx.timing_read(0)[1] == 2       # nothing recorded while off
+    assert_close(out, ref, "untimed decode", spread)
