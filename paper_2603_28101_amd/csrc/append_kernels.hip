@@ -162,7 +162,11 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   };
 
   // byte offsets of this thread's pieces inside a (block, kv head) pair of tiles: with the pair's
-  // address in scalar registers a load needs no vector address arithmetic
+  // address in scalar registers a load needs no vector address arithmetic (global_load with a
+  // scalar base and a 32-bit lane offset).  The compiler picks that form only if it sees, next to
+  // the load, a base that lives in scalar registers and a lane offset that is widened there: left
+  // alone it adds the loop-invariant 64-bit lane address to the block offset with a 64-bit vector
+  // add per load, hence the two empty asm statements in fetch().
   const uint32_t k_piece = static_cast<uint32_t>(k_tok * D + k_slice * 8) * 2u;
   const uint32_t v_piece = static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u;
   const char* pool_h = reinterpret_cast<const char*>(a.pool + h * head_stride);
@@ -175,9 +179,16 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
       // a block past the item's last one repeats that block (load_ids clamps): its keys are
       // masked as beyond every row's position, and its V pieces are cleared below
       const int blk = kChunkBlocks * c + x;
-      const char* t = pool_h + static_cast<int64_t>(ids[x]) * (block_stride * 2);
-      stage_k[x] = *reinterpret_cast<const u32x4*>(t + k_piece);
-      u32x4 vv = *reinterpret_cast<const u32x4*>(t + v_piece);
+      typedef const __attribute__((address_space(1))) char* gptr_t;
+      typedef const __attribute__((address_space(1))) u32x4* gvec_t;
+      uint64_t base = reinterpret_cast<uint64_t>(pool_h) +
+                      static_cast<uint64_t>(ids[x]) * static_cast<uint64_t>(block_stride * 2);
+      uint32_t kp = k_piece, vp = v_piece;
+      asm("" : "+s"(base));
+      asm("" : "+v"(kp), "+v"(vp));
+      const gptr_t t = reinterpret_cast<gptr_t>(base);
+      stage_k[x] = *reinterpret_cast<gvec_t>(t + kp);
+      u32x4 vv = *reinterpret_cast<gvec_t>(t + vp);
       if (decltype(may_pass_end)::value &&
           kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
         const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
