@@ -7,7 +7,7 @@ on the Qwen3-8B-shaped long-tail workload (64 trajectories, 32 query / 8 kv head
 head_dim 128, lognormal context lengths).  Inputs are synthetic and resident in HBM
 before the timed region.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4|5] [--op attention|pack] [--seed S]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2..8] [--op attention|pack|placement] [--seed S]
 """
 from __future__ import annotations
 

@@ -106,3 +106,28 @@ def test_empty_and_errors():
         dc.ctx.kv_pack(np.array([-1], dtype=np.int32), st)
     with pytest.raises(heddle.HeddleError):
         dc.ctx.kv_unpack(np.array([1, 1], dtype=np.int32), st)
+
+
+def test_pack_of_the_benchmark_workload_at_full_size():
+    """The launch `bench.py --op pack` times: every block of the Qwen3-8B decode workload (1.77 GB)
+    gathered in one call; all bytes compared, then scattered back into a cleared pool."""
+    torch = torch_mod()
+    case = hw.make_workload(2, 0, threads=16)
+    dc = DeviceCase(case)
+    used = np.concatenate([case["block_ids"][case["row_off"][b]:case["row_off"][b + 1]]
+                           for b in range(len(case["lens"]))]).astype(np.int32)
+    print("pack full size:", len(used), "blocks", flush=True)
+    st = _staging(len(used), case)
+    dc.ctx.kv_pack(used, st)
+    torch.cuda.synchronize()
+    got = bf16_to_host_bits(st).reshape((len(used),) + case["pool"].shape[1:])
+    assert np.array_equal(got, case["pool"][used])
+    del got
+    dc.pool.view(torch.int16).zero_()
+    dc.ctx.kv_unpack(used, st)
+    torch.cuda.synchronize()
+    back = bf16_to_host_bits(dc.pool).reshape(case["pool"].shape)
+    assert np.array_equal(back[used], case["pool"][used])
+    mask = np.ones(case["n_blocks"], dtype=bool)
+    mask[used] = False
+    assert not back[mask].any()
