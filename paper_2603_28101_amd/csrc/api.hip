@@ -22,6 +22,7 @@ constexpr int kEventPairs = 2048;      // per timed kernel; older records are ov
 
 struct StagingSlot {
   int32_t* host = nullptr;             // pinned
+  void* host_dev = nullptr;            // the same memory as the device addresses it
   size_t cap_words = 0;
   hipEvent_t done = nullptr;           // recorded after the H2D copy that reads `host`
   bool in_flight = false;
@@ -124,20 +125,25 @@ int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
     if (s.host != nullptr) HEDDLE_HIP(hipHostFree(s.host));
     s.host = nullptr;
     s.cap_words = 0;
-    const size_t cap = words + words / 2 + 1024;
+    const size_t cap = (words + words / 2 + 1024 + 3) & ~static_cast<size_t>(3);   // whole 16-byte pieces
     void* p = nullptr;
     if (hipHostMalloc(&p, cap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) return HEDDLE_E_NOMEM;
     s.host = static_cast<int32_t*>(p);
     s.cap_words = cap;
+    s.host_dev = nullptr;
+    HEDDLE_HIP(hipHostGetDevicePointer(&s.host_dev, p, 0));
   }
   *out = &s;
   return HEDDLE_OK;
 }
 
+// The image is copied by a kernel that reads the pinned buffer (see plan_copy_kernel), in whole
+// 16-byte pieces: both buffers are sized in multiples of four words.
 int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream) {
-  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, words, sizeof(int32_t));
+  const size_t padded = (words + 3) & ~static_cast<size_t>(3);
+  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
   if (rc != HEDDLE_OK) return rc;
-  HEDDLE_HIP(hipMemcpyAsync(ctx->dev_plan, s->host, words * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+  HEDDLE_HIP(launch_plan_copy(s->host_dev, ctx->dev_plan, padded / 4, stream));
   HEDDLE_HIP(hipEventRecord(s->done, stream));
   s->in_flight = true;
   return HEDDLE_OK;

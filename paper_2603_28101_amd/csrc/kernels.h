@@ -140,4 +140,8 @@ hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* i
 
 hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
 
+// Copies n_vec 16-byte pieces from pinned host memory (src, device-visible) to device memory in a
+// kernel on the caller's stream.
+hipError_t launch_plan_copy(const void* src, void* dst, size_t n_vec, hipStream_t stream);
+
 }  // namespace heddle
