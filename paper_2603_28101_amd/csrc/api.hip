@@ -24,7 +24,7 @@ struct StagingSlot {
   int32_t* host = nullptr;             // pinned
   void* host_dev = nullptr;            // the same memory as the device addresses it
   size_t cap_words = 0;
-  hipEvent_t done = nullptr;           // recorded after the H2D copy that reads `host`
+  hipEvent_t done = nullptr;           // recorded after the copy kernel that reads `host`
   bool in_flight = false;
 };
 
