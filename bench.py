@@ -127,9 +127,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events around every 4th launch of each kernel, on the launch stream (an event pair
-    # costs a few microseconds of stream time, so not every step carries one)
-    ctx.timing_enable(4)
+    # HIP events around every 8th launch of each kernel, on the launch stream (an event record
+    # costs several microseconds of stream time, so few steps carry one)
+    ctx.timing_enable(8)
     # a full Python garbage collection (tens of ms with torch loaded) must not land in the
     # timed region: collect now, keep the collector off while timing
     gc.collect()

@@ -16,6 +16,9 @@ using namespace heddle;
 namespace {
 
 constexpr int kStagingSlots = 8;
+constexpr int kUploadsPerGuard = 4;    // an event is recorded after every 4th plan upload only: a record
+                                       // costs about 3 us of stream time
+constexpr int kGuards = kStagingSlots / kUploadsPerGuard;
 constexpr int kTimedKernels = 8;       // split-K decode, combine, append, kv write, pack, unpack, shared prefix,
                                        // narrow append
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
@@ -24,8 +27,15 @@ struct StagingSlot {
   int32_t* host = nullptr;             // pinned
   void* host_dev = nullptr;            // the same memory as the device addresses it
   size_t cap_words = 0;
-  hipEvent_t done = nullptr;           // recorded after the copy kernel that reads `host`
-  bool in_flight = false;
+  uint64_t used_at = 0;                // number of the upload that last read `host`; 0: none pending
+};
+
+// Recorded on the stream after upload number `seq`: once it has completed, the copy kernels of
+// that upload and of all earlier ones have read their staging buffers.
+struct UploadGuard {
+  hipEvent_t done = nullptr;
+  uint64_t seq = 0;
+  bool pending = false;
 };
 
 struct KernelTimer {
@@ -46,6 +56,9 @@ struct heddle_ctx {
 
   StagingSlot staging[kStagingSlots];
   int next_slot = 0;
+  UploadGuard guards[kGuards];
+  int next_guard = 0;
+  uint64_t uploads = 0;
   int32_t* dev_plan = nullptr;
   size_t dev_plan_words = 0;
   float* dev_part_acc = nullptr;
@@ -113,13 +126,24 @@ int grow_device(void** ptr, size_t* have, size_t want, size_t elem_bytes) {
   return HEDDLE_OK;
 }
 
-// Takes the next pinned staging slot, waiting for the copy that last used it.
+// Takes the next pinned staging slot, waiting for the copy that last read it: for the oldest
+// guard recorded at or after that upload (with 8 slots and a guard every 4th upload there is
+// one unless calls failed in between; then the device is synchronised).
 int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
   StagingSlot& s = ctx->staging[ctx->next_slot];
   ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-  if (s.in_flight) {
-    HEDDLE_HIP(hipEventSynchronize(s.done));
-    s.in_flight = false;
+  if (s.used_at != 0) {
+    UploadGuard* cover = nullptr;
+    for (UploadGuard& g : ctx->guards)
+      if (g.seq >= s.used_at && (cover == nullptr || g.seq < cover->seq)) cover = &g;
+    if (cover == nullptr) {
+      HEDDLE_HIP(hipDeviceSynchronize());
+    } else if (cover->pending) {
+      HEDDLE_HIP(hipEventSynchronize(cover->done));
+      for (UploadGuard& g : ctx->guards)
+        if (g.seq <= cover->seq) g.pending = false;      // stream order: older guards have completed too
+    }
+    s.used_at = 0;
   }
   if (words > s.cap_words) {
     if (s.host != nullptr) HEDDLE_HIP(hipHostFree(s.host));
@@ -144,8 +168,14 @@ int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream) {
   int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
   if (rc != HEDDLE_OK) return rc;
   HEDDLE_HIP(launch_plan_copy(s->host_dev, ctx->dev_plan, padded / 4, stream));
-  HEDDLE_HIP(hipEventRecord(s->done, stream));
-  s->in_flight = true;
+  s->used_at = ++ctx->uploads;
+  if (ctx->uploads % kUploadsPerGuard == 0) {
+    UploadGuard& g = ctx->guards[ctx->next_guard];
+    ctx->next_guard = (ctx->next_guard + 1) % kGuards;
+    HEDDLE_HIP(hipEventRecord(g.done, stream));
+    g.seq = ctx->uploads;
+    g.pending = true;
+  }
   return HEDDLE_OK;
 }
 
@@ -209,7 +239,7 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
     DeviceGuard guard(cfg->device);
     if (!guard.ok()) return HEDDLE_E_HIP;
     if (n_cu == 0) HEDDLE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, cfg->device));
-    for (StagingSlot& s : ctx->staging) HEDDLE_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    for (UploadGuard& g : ctx->guards) HEDDLE_HIP(hipEventCreateWithFlags(&g.done, hipEventDisableTiming));
     ctx->has_device = true;
   } else if (n_cu == 0) {
     n_cu = 256;
@@ -234,10 +264,10 @@ int heddle_ctx_destroy(heddle_ctx* ctx) {
   if (ctx->has_device) {
     DeviceGuard guard(ctx->cfg.device);
     if (ctx->enqueued && hipDeviceSynchronize() != hipSuccess) rc = HEDDLE_E_HIP;
-    for (StagingSlot& s : ctx->staging) {
+    for (StagingSlot& s : ctx->staging)
       if (s.host) (void)hipHostFree(s.host);
-      if (s.done) (void)hipEventDestroy(s.done);
-    }
+    for (UploadGuard& g : ctx->guards)
+      if (g.done) (void)hipEventDestroy(g.done);
     if (ctx->dev_plan) (void)hipFree(ctx->dev_plan);
     if (ctx->dev_part_acc) (void)hipFree(ctx->dev_part_acc);
     if (ctx->dev_part_ml) (void)hipFree(ctx->dev_part_ml);
