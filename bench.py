@@ -127,9 +127,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events around every 8th launch of each kernel, on the launch stream (an event record
-    # costs several microseconds of stream time, so few steps carry one)
-    ctx.timing_enable(8)
+    # HIP events around every 8th launch of each kernel (every launch of a short run), on the
+    # launch stream: an event record costs several microseconds of stream time, so few steps carry one
+    ctx.timing_enable(max(1, min(8, args.steps // 25)))
     # a full Python garbage collection (tens of ms with torch loaded) must not land in the
     # timed region: collect now, keep the collector off while timing
     gc.collect()
