@@ -90,6 +90,10 @@ def main():
         dominant, bound = 4, "hbm"
     elif kind == "decode":
         lens = case["lens"]
+        # a decode step stores the K/V row of its own position (len - 1) before it attends
+        gen = torch.Generator(device="cuda").manual_seed(args.seed)
+        k_row = torch.randn((w.B, w.n_kv_heads, w.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        v_row = torch.randn((w.B, w.n_kv_heads, w.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
         unit_bytes = hw.kv_bytes(lens, w.n_kv_heads, w.head_dim)   # algorithmic bytes of one step
         shared = "group_of" in case
         if shared:
@@ -102,10 +106,10 @@ def main():
 
             def step():
                 ctx.attn_decode_shared(lens, case["row_off"], case["block_ids"], row_off, block_ids, q, out, None,
-                                       stream=stream)
+                                       k_row, v_row, stream=stream)
         else:
             def step():
-                ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+                ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, k_row, v_row, stream=stream)
 
         dominant, bound = 0, "hbm"
     else:
@@ -232,11 +236,11 @@ def main():
         # the same batch through the plain decode entry point, which reads a shared block once per
         # trajectory that names it
         for _ in range(5):
-            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, k_row, v_row, stream=stream)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         for _ in range(20):
-            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, stream=stream)
+            ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, k_row, v_row, stream=stream)
         torch.cuda.synchronize()
         plain_us = (time.perf_counter() - t2) * 1e6 / 20
         extra = {"kv_bytes_if_every_trajectory_read_its_own": logical_bytes,

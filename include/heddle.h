@@ -332,7 +332,8 @@ int heddle_simulate_group(int32_t n, const int32_t* lengths, int32_t n_prof, con
  * records every N-th launch of each kernel (each recorded launch costs two
  * event records, a few microseconds of stream time); 0 turns it off.
  * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
- * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write,
+ * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write of an
+ * append (a decode step's new rows are stored by the launch that uploads its plan),
  * 4 = pack, 5 = unpack, 6 = shared-prefix kernel, 7 = matrix-core kernel for tiles of few rows
  * (short chunks; decode with 8 query heads per kv head). */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);

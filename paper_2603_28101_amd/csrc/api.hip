@@ -163,11 +163,12 @@ int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
 
 // The image is copied by a kernel that reads the pinned buffer (see plan_copy_kernel), in whole
 // 16-byte pieces: both buffers are sized in multiples of four words.
-int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream) {
+// With `rows` the same launch stores the new K/V row of every trajectory of a decode step.
+int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream, const KvWriteLaunch* rows = nullptr) {
   const size_t padded = (words + 3) & ~static_cast<size_t>(3);
   int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
   if (rc != HEDDLE_OK) return rc;
-  HEDDLE_HIP(launch_plan_copy(s->host_dev, ctx->dev_plan, padded / 4, stream));
+  HEDDLE_HIP(launch_plan_copy(s->host_dev, ctx->dev_plan, padded / 4, rows, stream));
   s->used_at = ++ctx->uploads;
   if (ctx->uploads % kUploadsPerGuard == 0) {
     UploadGuard& g = ctx->guards[ctx->next_guard];
@@ -503,19 +504,14 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   }
   h_cu[B] = B;
   if (n_members > 0) std::memcpy(h_members, sp.members.data(), sizeof(int32_t) * n_members);
-  rc = upload(ctx, slot, words, stream);
-  if (rc != HEDDLE_OK) return rc;
-  const int32_t* d = ctx->dev_plan;
-  ctx->enqueued = true;
-
+  // the step's new K/V rows are stored by the launch that copies the plan image; its row writers
+  // read first_pos from the pinned image
+  KvWriteLaunch kw{};
   if (args->k_new != nullptr) {
-    KvWriteLaunch kw{};
     kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
     kw.row_off = args->row_off;
     kw.block_ids = args->block_ids;
-    kw.first_pos = d + (h_first - w);
-    kw.cu_rows = d + (h_cu - w);
-    kw.cu_wblk = kw.cu_rows;                 // one row, hence one block, per trajectory
+    kw.first_pos = static_cast<const int32_t*>(slot->host_dev) + (h_first - w);
     kw.k = static_cast<const uint16_t*>(args->k_new);
     kw.v = static_cast<const uint16_t*>(args->v_new);
     kw.B = B;
@@ -523,9 +519,12 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     kw.n_wblk = B;
     kw.n_kv_heads = ctx->cfg.n_kv_heads;
     kw.head_dim = D;
-    TimedScope t(ctx, 3, stream);
-    HEDDLE_HIP(launch_kv_write(kw, stream));
+    kw.one_row_each = 1;
   }
+  rc = upload(ctx, slot, words, stream, args->k_new != nullptr ? &kw : nullptr);
+  if (rc != HEDDLE_OK) return rc;
+  const int32_t* d = ctx->dev_plan;
+  ctx->enqueued = true;
 
   const float scale_log2 = ctx->scale * 1.4426950408889634f;
   const DecodeTrajRec* d_trajs = reinterpret_cast<const DecodeTrajRec*>(d + 8 * (n_items + n_gitems));
@@ -687,19 +686,14 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     h_cu[b] = b;
   }
   h_cu[B] = B;
-  rc = upload(ctx, slot, words, stream);
-  if (rc != HEDDLE_OK) return rc;
-  const int32_t* d = ctx->dev_plan;
-  ctx->enqueued = true;
-
+  // the step's new K/V rows are stored by the launch that copies the plan image; its row writers
+  // read first_pos from the pinned image
+  KvWriteLaunch kw{};
   if (args->k_new != nullptr) {
-    KvWriteLaunch kw{};
     kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
     kw.row_off = args->row_off;
     kw.block_ids = args->block_ids;
-    kw.first_pos = d + (h_first - w);
-    kw.cu_rows = d + (h_cu - w);
-    kw.cu_wblk = kw.cu_rows;                 // one row, hence one block, per trajectory
+    kw.first_pos = static_cast<const int32_t*>(slot->host_dev) + (h_first - w);
     kw.k = static_cast<const uint16_t*>(args->k_new);
     kw.v = static_cast<const uint16_t*>(args->v_new);
     kw.B = B;
@@ -707,9 +701,12 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     kw.n_wblk = B;
     kw.n_kv_heads = ctx->cfg.n_kv_heads;
     kw.head_dim = D;
-    TimedScope t(ctx, 3, stream);
-    HEDDLE_HIP(launch_kv_write(kw, stream));
+    kw.one_row_each = 1;
   }
+  rc = upload(ctx, slot, words, stream, args->k_new != nullptr ? &kw : nullptr);
+  if (rc != HEDDLE_OK) return rc;
+  const int32_t* d = ctx->dev_plan;
+  ctx->enqueued = true;
 
   DecodeLaunch dl{};
   dl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);

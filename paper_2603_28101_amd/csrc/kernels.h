@@ -59,6 +59,8 @@ struct KvWriteLaunch {
   const uint16_t* k;           // bf16 [n_rows][n_kv][d]
   const uint16_t* v;
   int32_t B, n_rows, n_wblk, n_kv_heads, head_dim;
+  int32_t one_row_each;        // 1: trajectory b brings exactly row b (a decode step); cu_rows and cu_wblk are
+                               // not read then
 };
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream);
 
@@ -141,7 +143,9 @@ hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* i
 hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
 
 // Copies n_vec 16-byte pieces from pinned host memory (src, device-visible) to device memory in a
-// kernel on the caller's stream.
-hipError_t launch_plan_copy(const void* src, void* dst, size_t n_vec, hipStream_t stream);
+// kernel on the caller's stream.  With rows != nullptr the same launch also stores one new K/V row
+// per trajectory (rows->one_row_each must be set); rows->first_pos must then point into memory
+// that is already valid when the kernel starts (the pinned image, not the copy's destination).
+hipError_t launch_plan_copy(const void* src, void* dst, size_t n_vec, const KvWriteLaunch* rows, hipStream_t stream);
 
 }  // namespace heddle

@@ -16,23 +16,34 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 // one head-dim element and stores them as one 16-byte piece of the [d][16] V tile; where the new
 // rows cover only part of those 8 slots the piece is read, merged and written back (the other
 // slots belong to the same trajectory and nobody else writes this block during the call).
-__global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
+__device__ __forceinline__ void kv_write_block(const KvWriteLaunch& a, int wg) {
   constexpr int kMaxD = 128;
   __shared__ __attribute__((aligned(16))) uint16_t s_v[16][kMaxD + 8];
-  const int wb = blockIdx.x / a.n_kv_heads;
-  const int h = blockIdx.x - wb * a.n_kv_heads;
-  int lo = 0, hi = a.B;                       // trajectory of this write block: last b with cu_wblk[b] <= wb
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.cu_wblk[mid] <= wb) lo = mid; else hi = mid;
+  const int wb = wg / a.n_kv_heads;
+  const int h = wg - wb * a.n_kv_heads;
+  int b, n_new, blk_in_traj;
+  int64_t row0;
+  if (a.one_row_each) {                       // a decode step: write block wb is trajectory wb's
+    b = wb;
+    n_new = 1;
+    blk_in_traj = 0;
+    row0 = b;
+  } else {
+    int lo = 0, hi = a.B;                     // trajectory of this write block: last b with cu_wblk[b] <= wb
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.cu_wblk[mid] <= wb) lo = mid; else hi = mid;
+    }
+    b = lo;
+    n_new = a.cu_rows[b + 1] - a.cu_rows[b];
+    blk_in_traj = wb - a.cu_wblk[b];
+    row0 = a.cu_rows[b];
   }
-  const int b = lo;
   const int first = a.first_pos[b];
-  const int n_new = a.cu_rows[b + 1] - a.cu_rows[b];
-  const int blk = first / 16 + (wb - a.cu_wblk[b]);          // logical block
+  const int blk = first / 16 + blk_in_traj;                  // logical block
   const int t_lo = max(first, blk * 16), t_hi = min(first + n_new, blk * 16 + 16);
   const int s_lo = t_lo - blk * 16, s_hi = t_hi - blk * 16;  // slots [s_lo, s_hi) of the block are new
-  const int64_t row_lo = static_cast<int64_t>(a.cu_rows[b]) + (t_lo - first);   // source row of slot s_lo
+  const int64_t row_lo = row0 + (t_lo - first);              // source row of slot s_lo
   const int D = a.head_dim;
   const int pieces = D / 8;
   const int phys = a.block_ids[a.row_off[b] + blk];
@@ -70,6 +81,8 @@ __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) {
   }
 }
 
+__global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) { kv_write_block(a, blockIdx.x); }
+
 // Gathers whole blocks of the pool into a contiguous staging buffer (PACK) or scatters them
 // back under a list of physical blocks.  One workgroup moves one 4 KB slice of a block, one
 // 16-byte non-temporal load and store per thread.
@@ -94,6 +107,19 @@ __global__ __launch_bounds__(256) void kv_move_kernel(uint16_t* pool, uint16_t* 
 __global__ __launch_bounds__(256) void plan_copy_kernel(const u32x4* src, u32x4* dst, uint32_t n_vec) {
   const uint32_t i = blockIdx.x * 256u + threadIdx.x;
   if (i < n_vec) dst[i] = src[i];
+}
+
+// The same copy and, in the workgroups behind it, the new K/V row of every trajectory of a decode
+// step: one launch instead of two in front of the attention kernel.  The row writers read their
+// trajectory's position from the pinned image (the device copy is being written meanwhile).
+__global__ __launch_bounds__(256) void plan_copy_rows_kernel(const u32x4* src, u32x4* dst, uint32_t n_vec,
+                                                              uint32_t copy_groups, KvWriteLaunch a) {
+  if (blockIdx.x < copy_groups) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n_vec) dst[i] = src[i];
+  } else {
+    kv_write_block(a, static_cast<int>(blockIdx.x - copy_groups));
+  }
 }
 
 constexpr int kStreamGroups = 2048;
@@ -151,11 +177,18 @@ hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* i
   return hipGetLastError();
 }
 
-hipError_t launch_plan_copy(const void* src, void* dst, size_t n_vec, hipStream_t stream) {
-  if (n_vec == 0) return hipSuccess;
+hipError_t launch_plan_copy(const void* src, void* dst, size_t n_vec, const KvWriteLaunch* rows, hipStream_t stream) {
   if (n_vec > 0x7fffffffu) return hipErrorInvalidValue;
-  const dim3 grid(static_cast<unsigned>((n_vec + 255) / 256));
-  hipLaunchKernelGGL(plan_copy_kernel, grid, dim3(256), 0, stream, static_cast<const u32x4*>(src),
+  const unsigned copy_groups = static_cast<unsigned>((n_vec + 255) / 256);
+  if (rows != nullptr && rows->n_wblk > 0) {
+    if (!rows->one_row_each || rows->head_dim > 128) return hipErrorInvalidValue;
+    const dim3 grid(copy_groups + static_cast<unsigned>(rows->n_wblk) * static_cast<unsigned>(rows->n_kv_heads));
+    hipLaunchKernelGGL(plan_copy_rows_kernel, grid, dim3(256), 0, stream, static_cast<const u32x4*>(src),
+                       static_cast<u32x4*>(dst), static_cast<uint32_t>(n_vec), copy_groups, *rows);
+    return hipGetLastError();
+  }
+  if (n_vec == 0) return hipSuccess;
+  hipLaunchKernelGGL(plan_copy_kernel, dim3(copy_groups), dim3(256), 0, stream, static_cast<const u32x4*>(src),
                      static_cast<u32x4*>(dst), static_cast<uint32_t>(n_vec));
   return hipGetLastError();
 }
