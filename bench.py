@@ -94,6 +94,8 @@ def main():
         gen = torch.Generator(device="cuda").manual_seed(args.seed)
         k_row = torch.randn((w.B, w.n_kv_heads, w.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
         v_row = torch.randn((w.B, w.n_kv_heads, w.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        case["k_row"] = k_row.view(torch.int16).cpu().numpy().view(np.uint16)      # for the oracle's timed pass
+        case["v_row"] = v_row.view(torch.int16).cpu().numpy().view(np.uint16)
         unit_bytes = hw.kv_bytes(lens, w.n_kv_heads, w.head_dim)   # algorithmic bytes of one step
         shared = "group_of" in case
         if shared:
@@ -415,6 +417,8 @@ def cpu_baseline(case, w, np, kind, unit):
         done_bytes, n_done = 0, 0
         for b in range(len(lens)):
             pairs = [(b, j) for j in range(w.n_q_heads)]
+            oa.write_kv(case["pool"], case["row_off"], case["block_ids"], [int(lens[b]) - 1], b,
+                        case["k_row"][b:b + 1], case["v_row"][b:b + 1])
             oa.decode_rows(case["pool"], case["row_off"], case["block_ids"], lens, case["q"], w.n_kv_heads, pairs)
             done_bytes += int(lens[b]) * 2 * w.n_kv_heads * w.head_dim * 2
             n_done += 1
