@@ -7,7 +7,7 @@ on the Qwen3-8B-shaped long-tail workload (64 trajectories, 32 query / 8 kv head
 head_dim 128, lognormal context lengths).  Inputs are synthetic and resident in HBM
 before the timed region.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2..8] [--op attention|pack|placement] [--seed S]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2..9] [--op attention|pack|placement] [--seed S]
 """
 from __future__ import annotations
 
@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8, 9])
     ap.add_argument("--op", default="attention", choices=["attention", "pack", "placement"],
                     help="attention: the workload's decode or append pass (default); pack: gather of every "
                          "trajectory's blocks into one contiguous staging buffer (whole-block copy); placement: decode step time per batch size -> interference table -> "

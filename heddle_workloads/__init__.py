@@ -48,6 +48,7 @@ WORKLOADS = {
     6: Workload(6, "grpo-group-decode", "decode", 128, 32, 8, 128),
     7: Workload(7, "verify-4-tokens", "append", 64, 32, 8, 128),
     8: Workload(8, "straggler-append", "append", 1, 32, 8, 128),
+    9: Workload(9, "qwen3-14b-decode", "decode", 64, 40, 8, 128),
 }
 
 GROUP_SAMPLES = 16   # samples per prompt (Sec. 7, Workloads)
@@ -101,6 +102,8 @@ def draw_lengths(cfg_id: int, rng: np.random.Generator):
         return _lognormal_lengths(rng, 64, 4096, 1.0, 256, 32768), np.full(64, 4, dtype=np.int64)
     if cfg_id == 8:   # one long-tail trajectory alone on the GPU receives a short tool output
         return rng.integers(100000, 120001, 1).astype(np.int64), rng.integers(32, 65, 1).astype(np.int64)
+    if cfg_id == 9:   # the length law of workload 2 under the Qwen3-14B head shape (5 query heads per kv head)
+        return _lognormal_lengths(rng, 64, 4096, 1.0, 256, 32768), None
     raise ValueError(f"unknown workload {cfg_id}")
 
 

@@ -67,7 +67,10 @@ extern "C" {
 typedef struct heddle_ctx heddle_ctx;
 
 typedef struct heddle_config {
-  int32_t n_q_heads;      /* multiple of n_kv_heads; group size G = n_q/n_kv in {1,2,4,8} */
+  int32_t n_q_heads;      /* multiple of n_kv_heads; query heads per kv head G = n_q/n_kv: with head_dim
+                             128 any G from 1 to 32 (decode for G other than 1, 2, 4, 8 needs tile_blk
+                             to be a multiple of 4; append needs head_dim 128); with head_dim 64
+                             G in {1,2,4,8}, decode only.  Else HEDDLE_E_UNSUPPORTED. */
   int32_t n_kv_heads;
   int32_t head_dim;       /* 64 or 128 */
   int32_t block_tokens;   /* must be 16 */
@@ -224,8 +227,10 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
  *     (group items, sorted by (-(blk_end-blk_begin), g, k, tile)).
  *  6. trajectory b: cut(nblk[b]-prefix[b], chunk) -> parts over [prefix[b] + k*per, ...)
  *     with slot = parts_g + k; nsplit[b] = parts_g + count; items sorted as before.
- * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape the
- * matrix-core kernel does not support (head_dim != 128) no groups are formed. */
+ * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape one
+ * of the two kernels involved is not built for (head_dim != 128, or G other than
+ * 1, 2, 4, 8) no groups are formed, and heddle_attn_decode_shared is then
+ * heddle_attn_decode. */
 typedef struct heddle_shared_plan {
   int32_t  cap_items, cap_gitems, cap_groups;          /* in  */
   int32_t  n_items, n_gitems, n_groups, chunk, chunk_g; /* out */

@@ -222,8 +222,16 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
     return HEDDLE_E_INVAL;
   if (cfg->device < -1 || (cfg->device >= 0 && cfg->kv_pool == nullptr)) return HEDDLE_E_INVAL;
   if (!(cfg->scale >= 0.f) || !std::isfinite(cfg->scale)) return HEDDLE_E_INVAL;
-  if (cfg->device >= 0 && !decode_shape_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim))
-    return HEDDLE_E_UNSUPPORTED;
+  // Head shapes the packed-dot decode kernel is not built for (3, 5, 6, 7 ... query heads per kv
+  // head) decode on the matrix-core kernel, which cuts keys at multiples of 64: the plan's parts
+  // must then start there.
+  if (cfg->device >= 0) {
+    const int32_t group = cfg->n_q_heads / cfg->n_kv_heads;
+    const int32_t tile_blk = cfg->tile_blk ? cfg->tile_blk : 4;
+    const bool on_mfma_only = append_shape_supported(group, cfg->head_dim) &&
+                              tile_blk % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
+    if (!decode_shape_supported(group, cfg->head_dim) && !on_mfma_only) return HEDDLE_E_UNSUPPORTED;
+  }
 
   std::unique_ptr<heddle_ctx> ctx(new (std::nothrow) heddle_ctx);
   if (!ctx) return HEDDLE_E_NOMEM;
@@ -373,7 +381,7 @@ int check_decode_args(const heddle_ctx* ctx, const heddle_decode_args* args) {
 void plan_shared_for(const heddle_ctx* ctx, int32_t B, const int32_t* len, const int32_t* row_off,
                      const int32_t* block_ids, SharedPlan& out) {
   const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
-  const bool can_group = append_shape_supported(G, ctx->cfg.head_dim);
+  const bool can_group = append_shape_supported(G, ctx->cfg.head_dim) && decode_shape_supported(G, ctx->cfg.head_dim);
   const int32_t tile_members = can_group ? append_tile_rows(G) : 1;
   plan_decode_shared(ctx->plan, can_group ? ctx->min_share_blk : INT32_MAX, ctx->group_wg_per_cu, tile_members, B,
                      len, row_off, block_ids, out);
@@ -441,6 +449,10 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   int rc = check_decode_args(ctx, args);
   if (rc != HEDDLE_OK) return rc;
   if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
+  // the private blocks go through the packed-dot kernel: head shapes it is not built for decode
+  // without sharing
+  if (!decode_shape_supported(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads, ctx->cfg.head_dim))
+    return heddle_attn_decode(ctx, args, hip_stream);
   const int32_t B = args->B;
 
   DeviceGuard guard(ctx->cfg.device);
@@ -652,9 +664,13 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   // With 8 query heads per kv head the packed-dot kernel is bound by its arithmetic; the
   // matrix-core kernel for short-row tiles, fed the same plan as an append of one token per
   // trajectory, is not.  It cuts keys at multiples of 64, so every item must start there.
-  bool on_matrix_cores = Hq / ctx->cfg.n_kv_heads == 8 && D == 128;
+  // Head shapes the packed-dot kernel is not built for (any other number of query heads per kv
+  // head up to 32, d = 128) run there too; the context was only created if its plans qualify.
+  const bool splitk_built = decode_shape_supported(Hq / ctx->cfg.n_kv_heads, D);
+  bool on_matrix_cores = (Hq / ctx->cfg.n_kv_heads == 8 || !splitk_built) && D == 128;
   for (size_t i = 0; i < n_items && on_matrix_cores; ++i)
     on_matrix_cores = ctx->items[i].blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
+  if (!on_matrix_cores && !splitk_built) return HEDDLE_E_UNSUPPORTED;
   for (size_t i = 0; i < n_items; ++i) {
     const DecodeItem& it = ctx->items[i];
     if (on_matrix_cores) {

@@ -7,8 +7,9 @@
 // K/V rows have been stored into the paged pool before this kernel runs.
 //
 // Work decomposition.  One workgroup (4 waves) owns a tile of 128 "rows": the G query heads
-// of one kv head times 128/G consecutive chunk rows, so the K/V bytes it reads are shared by
-// all G heads.  Tiles arrive longest-first from the host plan.
+// of one kv head times 128/G consecutive chunk rows (rounded down: with G = 5, 25 rows per head and
+// 3 idle rows), so the K/V bytes it reads are shared by all G heads.  G is a launch parameter, any
+// value from 1 to 32.  Tiles arrive longest-first from the host plan.
 //
 // Transposed formulation.  Per 32 keys (two such tiles per 64-key main-loop step) the wave
 // computes S^T = K Q^T (M = keys, N = query
@@ -42,6 +43,8 @@ constexpr int kBlockTokens = 16;
 constexpr int kChunkBlocks = 4;
 constexpr int kChunkTokens = kChunkBlocks * kBlockTokens;   // keys per main-loop step
 constexpr int kTileRows = 128;          // query rows (heads x chunk rows) per workgroup
+constexpr int kMaxGroup = 32;           // query heads per kv head: a tile of the kernel for short-row tiles holds
+                                        // one row of every head
 constexpr float kLazyMaxSlack = 8.0f;   // log2 units
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -57,13 +60,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // output) or against one part of them (split-K partial, merged by decode_combine_kernel).
 // Launch = GroupLaunch: the decode queries of the trajectories of a group against a range of the
 // blocks they share (whole blocks, every key visible to every row), split-K partial output.
-template <int G, int D, typename Launch>
+template <int D, typename Launch>
 __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   static_assert(D == 128, "staging roles and swizzle are written for head_dim 128");
   constexpr bool kGroup = std::is_same<Launch, GroupLaunch>::value;
   constexpr int NK = D / 16;             // MFMA steps over d for S^T
   constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
-  constexpr int R = kTileRows / G;       // chunk rows per workgroup tile
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int R = kTileRows / G;           // chunk rows per workgroup tile
   constexpr int kTileElems = kBlockTokens * D;
   constexpr int kStageK = kChunkTokens * D;            // elements of K per LDS stage
   constexpr int kStageV = kChunkBlocks * kTileElems;   // elements of V per LDS stage
@@ -88,7 +92,8 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
 
   // this lane's query row: head g of the kv head's group, row r_in_tile of the tile
   const int n_global = wave * 32 + n;
-  const int g = n_global / R;
+  const bool lane_used = n_global < G * R;           // the last 128 - G*R rows of the tile carry nothing
+  const int g = min(n_global / R, G - 1);
   const int r_in_tile = n_global - g * R;
   const int head = h * G + g;
 
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
     nsplit = rec.nsplit;
     part = rec.slot0 + min(r_in_tile, rows_n - 1) * nsplit;
   }
-  const bool row_valid = r_in_tile < rows_n;
+  const bool row_valid = lane_used && r_in_tile < rows_n;
 
   // Q^T operand: B[k = d][n = row], 8 consecutive d per lane and step
   bf16x8 qb[NK];
@@ -354,51 +359,31 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   }
 }
 
-template <int G, int D>
-hipError_t launch_append_t(const AppendLaunch& a, hipStream_t stream) {
+template <typename Launch>
+hipError_t launch_t(const Launch& a, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
-  hipLaunchKernelGGL((append_attn_kernel<G, D, AppendLaunch>), grid, dim3(256), 0, stream, a);
-  return hipGetLastError();
-}
-
-template <int G, int D>
-hipError_t launch_group_t(const GroupLaunch& a, hipStream_t stream) {
-  const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
-  hipLaunchKernelGGL((append_attn_kernel<G, D, GroupLaunch>), grid, dim3(256), 0, stream, a);
+  hipLaunchKernelGGL((append_attn_kernel<128, Launch>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
 bool append_shape_supported(int32_t group, int32_t head_dim) {
-  return head_dim == 128 && (group == 1 || group == 2 || group == 4 || group == 8);
+  return head_dim == 128 && group >= 1 && group <= kMaxGroup;
 }
 
 int32_t append_tile_rows(int32_t group) { return kTileRows / group; }
 
 hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream) {
-  const int G = a.n_q_heads / a.n_kv_heads;
-  if (a.head_dim != 128) return hipErrorInvalidValue;
-  switch (G) {
-    case 1: return launch_append_t<1, 128>(a, stream);
-    case 2: return launch_append_t<2, 128>(a, stream);
-    case 4: return launch_append_t<4, 128>(a, stream);
-    case 8: return launch_append_t<8, 128>(a, stream);
-  }
-  return hipErrorInvalidValue;
+  if (a.n_items <= 0) return hipSuccess;
+  if (!append_shape_supported(a.n_q_heads / a.n_kv_heads, a.head_dim)) return hipErrorInvalidValue;
+  return launch_t(a, stream);
 }
 
 hipError_t launch_group_attn(const GroupLaunch& a, hipStream_t stream) {
   if (a.n_items <= 0) return hipSuccess;
-  const int G = a.n_q_heads / a.n_kv_heads;
-  if (a.head_dim != 128) return hipErrorInvalidValue;
-  switch (G) {
-    case 1: return launch_group_t<1, 128>(a, stream);
-    case 2: return launch_group_t<2, 128>(a, stream);
-    case 4: return launch_group_t<4, 128>(a, stream);
-    case 8: return launch_group_t<8, 128>(a, stream);
-  }
-  return hipErrorInvalidValue;
+  if (!append_shape_supported(a.n_q_heads / a.n_kv_heads, a.head_dim)) return hipErrorInvalidValue;
+  return launch_t(a, stream);
 }
 
 }  // namespace heddle

@@ -56,12 +56,13 @@ struct KvTile {            // one 32-key tile in flight: 16 x 16 B per lane
 
 __device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
 
-template <int G, int D>
+template <int D>
 __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   static_assert(D == 128, "operand mapping is written for head_dim 128");
   constexpr int NK = D / 16;
   constexpr int NMT = D / 32;
-  constexpr int RS = kRows / G;                      // chunk rows per workgroup tile
+  const int G = a.n_q_heads / a.n_kv_heads;          // 1 .. 32
+  const int RS = kRows / G;                          // chunk rows per workgroup tile (rounded down: rows past G*RS idle)
   constexpr int kTileElems = kBlockTokens * D;
 
   // merge buffer: [wave][mt][j][lane] accumulators, then [wave][3][lane] (max, rounded sum, sum).  During the
@@ -89,9 +90,9 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   const const_ids_t ctable = (const_ids_t)(reinterpret_cast<uintptr_t>(a.block_ids + a.row_off[b]));
 
   // this lane's query row
-  const int g = n / RS;
+  const int g = min(n / RS, G - 1);
   const int r_in_tile = n - g * RS;
-  const bool row_valid = r_in_tile < rows_n;
+  const bool row_valid = n < G * RS && r_in_tile < rows_n;
   const int chunk_row = rec.row0 + min(r_in_tile, rows_n - 1);
   const int64_t q_row = static_cast<int64_t>(a.cu_chunk[b]) + chunk_row;
   const int pos = L + chunk_row;                                // last key this row may see
@@ -306,13 +307,6 @@ __global__ __launch_bounds__(256, 2) void narrow_attn_kernel(AppendLaunch a) {
   }
 }
 
-template <int G>
-hipError_t launch_narrow_t(const AppendLaunch& a, hipStream_t stream) {
-  const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
-  hipLaunchKernelGGL((narrow_attn_kernel<G, 128>), grid, dim3(256), 0, stream, a);
-  return hipGetLastError();
-}
-
 }  // namespace
 
 int32_t narrow_tile_rows(int32_t group) { return kRows / group; }
@@ -320,14 +314,10 @@ int32_t narrow_tile_rows(int32_t group) { return kRows / group; }
 hipError_t launch_narrow_attn(const AppendLaunch& a, hipStream_t stream) {
   if (a.n_items <= 0) return hipSuccess;
   const int G = a.n_q_heads / a.n_kv_heads;
-  if (a.head_dim != 128) return hipErrorInvalidValue;
-  switch (G) {
-    case 1: return launch_narrow_t<1>(a, stream);
-    case 2: return launch_narrow_t<2>(a, stream);
-    case 4: return launch_narrow_t<4>(a, stream);
-    case 8: return launch_narrow_t<8>(a, stream);
-  }
-  return hipErrorInvalidValue;
+  if (a.head_dim != 128 || G < 1 || G > kRows) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
+  hipLaunchKernelGGL((narrow_attn_kernel<128>), grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
 }
 
 }  // namespace heddle

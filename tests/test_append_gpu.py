@@ -30,7 +30,8 @@ RAGGED_L = [0, 1, 15, 16, 17, 100, 0, 500, 33, 1000]
 RAGGED_C = [1, 40, 1, 16, 33, 31, 130, 7, 64, 129]
 
 
-@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8)])
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8), (6, 2), (10, 2), (40, 8), (12, 2), (14, 2),
+                                      (24, 1), (32, 1)])
 def test_ragged_append_all_head_shapes(n_q, n_kv):
     c = small(40, RAGGED_L, RAGGED_C, n_q=n_q, n_kv=n_kv)
     print("append ragged", n_q, n_kv, flush=True)
@@ -196,7 +197,7 @@ def test_single_long_trajectory_short_chunk_is_split_and_exact():
     assert_lse_close(lse, ref_lse, "split append lse")
 
 
-@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8)])
+@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8), (6, 2), (10, 2), (40, 8), (14, 2), (32, 1)])
 def test_short_multi_token_decode(n_q, n_kv):
     """A verify step of speculative decoding: 2-8 new tokens on each of a few trajectories of very
     different lengths (ragged parts, L = 0 among them); default plan and one forced into many parts."""

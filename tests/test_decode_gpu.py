@@ -173,7 +173,7 @@ def test_back_to_back_calls_share_scratch_safely():
     assert_close(d_big.decode()[0], ref_big, "big again", sp_big)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 9])
 def test_full_size_workloads_sampled(cfg):
     """The named workloads at full size, in the launch configuration the benchmark times
     (default plan).  The oracle evaluates sampled (trajectory, head) pairs."""
@@ -276,3 +276,45 @@ def test_kernel_timers_count_and_time_the_launches():
     out, _ = dc.decode()
     assert dc.ctx.timing_read(0)[1] == 2       # nothing recorded while off
     assert_close(out, ref, "untimed decode", spread)
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(6, 2), (10, 2), (40, 8), (12, 2), (14, 2), (24, 1), (32, 1)])
+def test_ragged_lengths_other_head_groups(n_q, n_kv):
+    """3, 5, 6, 7, 12, 24 and 32 query heads per kv head (40/8 is the Qwen3-14B shape): the step runs
+    on the matrix-core kernel, default plan and one forced into many parts (parts start at
+    multiples of 4 blocks there)."""
+    c = small(12, RAGGED, n_q, n_kv, 128)
+    print("ragged, other head groups", n_q, n_kv, flush=True)
+    ref, ref_lse, spread = oa.decode(c["pool"], c["row_off"], c["block_ids"], c["lens"], c["q"], n_kv, with_spread=True,
+                                     centered=None)
+    for kw in (dict(), dict(n_cu=64, wg_per_cu=8, min_chunk_blk=4, tile_blk=4, max_split=64),
+               dict(n_cu=8, wg_per_cu=1, min_chunk_blk=8, tile_blk=8, max_split=3)):
+        dc = DeviceCase(c, **kw)
+        out, lse = dc.decode()
+        assert_close(out, ref, f"ragged {kw}", spread)
+        assert_lse_close(lse, ref_lse, f"ragged lse {kw}")
+    # the step's new rows, then the pool bit for bit
+    rng = np.random.default_rng(5)
+    B = len(RAGGED)
+    k_bits = hw.f32_to_bf16_bits(rng.standard_normal((B, n_kv, 128), dtype=np.float32))
+    v_bits = hw.f32_to_bf16_bits(rng.standard_normal((B, n_kv, 128), dtype=np.float32))
+    pool = c["pool"].copy()
+    for b in range(B):
+        oa.write_kv(pool, c["row_off"], c["block_ids"], [int(c["lens"][b]) - 1], b, k_bits[b:b + 1], v_bits[b:b + 1])
+    out, lse = dc.decode(k_new=to_dev_bf16(k_bits), v_new=to_dev_bf16(v_bits))
+    ref, ref_lse, spread = oa.decode(pool, c["row_off"], c["block_ids"], c["lens"], c["q"], n_kv, with_spread=True,
+                                     centered=None)
+    assert np.array_equal(dc.pool_bits(), pool)
+    assert_close(out, ref, "with new rows", spread)
+
+
+def test_head_shapes_no_kernel_is_built_for_are_refused():
+    import paper_2603_28101_amd as heddle
+    torch = __import__("torch")
+    pool = torch.zeros((4, 2, 2, 16 * 64), dtype=torch.bfloat16, device="cuda")
+    for n_q, n_kv, d, kw in ((6, 2, 64, {}),                    # 3 heads per kv head at d = 64
+                             (10, 2, 128, dict(tile_blk=2)),    # parts that would not start at multiples of 64 keys
+                             (66, 2, 128, {})):                 # 33 heads per kv head
+        with pytest.raises(heddle.HeddleError) as e:
+            heddle.Context(n_q, n_kv, d, 4, kv_pool=pool, device=0, **kw)
+        assert e.value.code == heddle.E_UNSUPPORTED, (n_q, n_kv, d)

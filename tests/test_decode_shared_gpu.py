@@ -150,3 +150,19 @@ def test_grpo_workload_sampled():
     out2, lse2 = dc.decode()
     assert np.abs(lse - lse2).max() < 2e-3
     assert np.abs(out - out2).max() < 2e-2
+
+
+def test_other_head_groups_decode_without_sharing():
+    """5 query heads per kv head: the private blocks would need the packed-dot kernel, which is not
+    built for it; the call is then plain decode (bit for bit) and the plan reports no group."""
+    lens = [16 * 20 + 5] * 6 + [700]
+    c = shared_case(21, lens, [0] * 6 + [-1], [20], n_q=10, n_kv=2)
+    dc = DeviceCase(c)
+    plan = dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])
+    assert plan["n_groups"] == 0
+    out, lse = run_shared(dc)
+    plain, plain_lse = DeviceCase(c).decode()
+    assert np.array_equal(out, plain) and np.array_equal(lse, plain_lse)
+    ref, ref_lse, spread = oracle_decode(c)
+    assert_close(out, ref, "G = 5 shared call", spread)
+    assert_lse_close(lse, ref_lse, "G = 5 shared call lse")
