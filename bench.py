@@ -151,7 +151,8 @@ def main():
     timer_of_kernel = dominant
     kernel_name = {0: "decode_splitk_kernel", 2: "append_attn_kernel", 4: "kv_move_kernel"}[dominant]
     if kind == "decode" and n_launch == 0:
-        # with 8 query heads per kv head the library runs decode in the matrix-core kernel for short-row tiles
+        # with 8 query heads per kv head (or 3, 5, 6, 7 ...) the library runs decode in the matrix-core kernel
+        # for short-row tiles
         (kernel_us, n_launch), kernel_name, timer_of_kernel = ctx.timing_read(7), "narrow_attn_kernel", 7
     if kind == "append":
         # tiles of at most 32 query rows per kv head run in the kernel that splits the keys over its waves

@@ -340,7 +340,8 @@ int heddle_simulate_group(int32_t n, const int32_t* lengths, int32_t n_prof, con
  * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write of an
  * append (a decode step's new rows are stored by the launch that uploads its plan),
  * 4 = pack, 5 = unpack, 6 = shared-prefix kernel, 7 = matrix-core kernel for tiles of few rows
- * (short chunks; decode with 8 query heads per kv head). */
+ * (short chunks; decode with 8 query heads per kv head or a number of them the
+ * split-K kernel is not built for). */
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
 int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
 /* The recorded launches one by one: writes the durations (microseconds) of up to
