@@ -214,7 +214,8 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
  *  2. Walking b upwards, the first trajectory with shareable >= 1 whose first block
  *     id is new leads that id; a later trajectory with the same first id joins the
  *     leader's group iff lcp >= min_share_blk, lcp = number of leading table entries
- *     equal to the leader's, capped by both shareable counts.  A group exists iff
+ *     equal to the leader's, capped by both shareable counts and, in a context whose
+ *     G is not 1, 2, 4 or 8, rounded down to a multiple of 4.  A group exists iff
  *     someone joined; prefix p_g = min lcp of the joined; members ascending;
  *     groups numbered by ascending leader.
  *  3. chunk from W = sum_b (nblk[b] - prefix[b]) as in heddle_plan_decode; chunk_g
@@ -227,10 +228,8 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
  *     (group items, sorted by (-(blk_end-blk_begin), g, k, tile)).
  *  6. trajectory b: cut(nblk[b]-prefix[b], chunk) -> parts over [prefix[b] + k*per, ...)
  *     with slot = parts_g + k; nsplit[b] = parts_g + count; items sorted as before.
- * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape one
- * of the two kernels involved is not built for (head_dim != 128, or G other than
- * 1, 2, 4, 8) no groups are formed, and heddle_attn_decode_shared is then
- * heddle_attn_decode. */
+ * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape the
+ * matrix-core kernel is not built for (head_dim != 128) no groups are formed. */
 typedef struct heddle_shared_plan {
   int32_t  cap_items, cap_gitems, cap_groups;          /* in  */
   int32_t  n_items, n_gitems, n_groups, chunk, chunk_g; /* out */

@@ -94,7 +94,7 @@ def plan_append(ctx_lens, chunk_lens, tile_rows: int):
 
 def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: int, n_cu=256,
                        wg_per_cu=4, min_chunk_blk=16, tile_blk=4, max_split=64, min_share_blk=4,
-                       group_wg_per_cu=1):
+                       group_wg_per_cu=1, prefix_align=1):
     """Split-K plan for a decode step in which trajectories whose block-table rows begin with
     the same physical blocks (the samples of one prompt, Sec. 7 Workloads; a prefix-cache hit
     in the sense of Sec. 2.3) read that shared prefix once per group instead of once each.
@@ -104,7 +104,9 @@ def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: 
          position of the step's own row (the block that row is written to is never shared).
       2. Walk b upwards.  The first trajectory whose first block id has not been seen is the
          leader of that id.  For a later trajectory with the same first id, lcp = number of
-         leading table entries equal to the leader's, capped by both shareable counts; it joins
+         leading table entries equal to the leader's, capped by both shareable counts and
+         rounded down to a multiple of prefix_align (the kernel that reads the private blocks
+         of some head shapes starts only at such blocks); it joins
          the leader's group iff lcp >= min_share_blk.  A group exists iff someone joined; its
          prefix p = min lcp over the joined; members = leader + joined, ascending b.
          Groups are numbered by ascending leader.  prefix[b] = p for members, else 0.
@@ -143,7 +145,8 @@ def plan_decode_shared(lens, row_off, block_ids, n_kv_heads: int, tile_members: 
         n = 0
         while n < cap and int(block_ids[row_off[a] + n]) == int(block_ids[row_off[b] + n]):
             n += 1
-        if n >= min_share_blk:
+        n = (n // prefix_align) * prefix_align
+        if n >= min_share_blk and n >= 1:
             joined.setdefault(a, []).append(b)
             lcp_of[b] = n
     leaders = sorted(joined)

@@ -376,15 +376,26 @@ int check_decode_args(const heddle_ctx* ctx, const heddle_decode_args* args) {
   return HEDDLE_OK;
 }
 
+// True if this context's private blocks (and plain decode) run on the matrix-core kernel for
+// short-row tiles only: a head shape the packed-dot kernel has no lane layout for.
+bool private_on_matrix_cores(const heddle_ctx* ctx) {
+  return !decode_shape_supported(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+}
+
 // Group formation of the shared-prefix plan with this context's parameters; on shapes the
-// matrix-core kernel is not built for nobody is grouped.
+// matrix-core kernel is not built for nobody is grouped.  Where the private blocks are read by
+// the matrix-core kernel, which starts at multiples of 64 keys, shared prefixes end at
+// multiples of 4 blocks.
 void plan_shared_for(const heddle_ctx* ctx, int32_t B, const int32_t* len, const int32_t* row_off,
                      const int32_t* block_ids, SharedPlan& out) {
   const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
-  const bool can_group = append_shape_supported(G, ctx->cfg.head_dim) && decode_shape_supported(G, ctx->cfg.head_dim);
+  const int32_t step_blk = kAppendStepKeys / HEDDLE_BLOCK_TOKENS;
+  const bool mfma_private = private_on_matrix_cores(ctx);
+  const bool can_group = append_shape_supported(G, ctx->cfg.head_dim) &&
+                         (!mfma_private || ctx->plan.tile_blk % step_blk == 0);
   const int32_t tile_members = can_group ? append_tile_rows(G) : 1;
-  plan_decode_shared(ctx->plan, can_group ? ctx->min_share_blk : INT32_MAX, ctx->group_wg_per_cu, tile_members, B,
-                     len, row_off, block_ids, out);
+  plan_decode_shared(ctx->plan, can_group ? ctx->min_share_blk : INT32_MAX, ctx->group_wg_per_cu, tile_members,
+                     mfma_private ? step_blk : 1, B, len, row_off, block_ids, out);
 }
 
 }  // namespace
@@ -449,11 +460,8 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   int rc = check_decode_args(ctx, args);
   if (rc != HEDDLE_OK) return rc;
   if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
-  // the private blocks go through the packed-dot kernel: head shapes it is not built for decode
-  // without sharing
-  if (!decode_shape_supported(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads, ctx->cfg.head_dim))
-    return heddle_attn_decode(ctx, args, hip_stream);
   const int32_t B = args->B;
+  const bool mfma_private = private_on_matrix_cores(ctx);
 
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;
@@ -487,6 +495,19 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   int32_t* h_members = h_cu + B + 1;
   for (size_t i = 0; i < n_items; ++i) {
     const DecodeItem& it = sp.items[i];
+    if (mfma_private) {       // the item as the matrix-core kernel reads it: one new token of trajectory b
+      if (it.blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) != 0) return HEDDLE_E_UNSUPPORTED;
+      AppendItemRec& r = reinterpret_cast<AppendItemRec*>(w)[i];
+      r.b = it.b;
+      r.row0 = 0;
+      r.rows_n = 1;
+      r.key_end = std::min(args->len_host[it.b], it.blk_end * HEDDLE_BLOCK_TOKENS);
+      r.step_begin = it.blk_begin / (kAppendStepKeys / HEDDLE_BLOCK_TOKENS);
+      r.slot0 = sp.part_off[it.b] + it.s;
+      r.nsplit = sp.nsplit[it.b];
+      r.pad = 0;
+      continue;
+    }
     DecodeItemRec& r = h_items[i];
     r.b = it.b;
     r.slot = sp.part_off[it.b] + it.s;
@@ -575,7 +596,27 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   dl.n_kv_heads = ctx->cfg.n_kv_heads;
   dl.head_dim = D;
   dl.scale_log2 = scale_log2;
-  {
+  if (mfma_private) {
+    AppendLaunch al{};                         // the private blocks seen as an append: L = len - 1, one new row each
+    al.pool = dl.pool;
+    al.row_off = args->row_off;
+    al.block_ids = args->block_ids;
+    al.ctx_len = d + (h_first - w);
+    al.cu_chunk = d + (h_cu - w);
+    al.items = reinterpret_cast<const AppendItemRec*>(d);
+    al.q = dl.q;
+    al.out = dl.out;
+    al.lse = dl.lse;
+    al.part_acc = dl.part_acc;
+    al.part_ml = dl.part_ml;
+    al.n_items = dl.n_items;
+    al.n_q_heads = Hq;
+    al.n_kv_heads = dl.n_kv_heads;
+    al.head_dim = D;
+    al.scale_log2 = scale_log2;
+    TimedScope t(ctx, 7, stream);
+    HEDDLE_HIP(launch_narrow_attn(al, stream));
+  } else {
     TimedScope t(ctx, 0, stream);
     HEDDLE_HIP(launch_decode_splitk(dl, stream));
   }

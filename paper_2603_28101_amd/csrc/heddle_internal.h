@@ -52,8 +52,8 @@ struct SharedPlan {
   std::vector<GroupItem> gitems;
 };
 void plan_decode_shared(const PlanParams& p, int32_t min_share_blk, int32_t group_wg_per_cu, int32_t tile_members,
-                        int32_t B, const int32_t* len, const int32_t* row_off, const int32_t* block_ids,
-                        SharedPlan& out);
+                        int32_t prefix_align, int32_t B, const int32_t* len, const int32_t* row_off,
+                        const int32_t* block_ids, SharedPlan& out);
 
 struct AppendTile {
   int32_t b, row0, rows, extent;

@@ -49,8 +49,8 @@ void plan_decode(const PlanParams& p, int32_t B, const int32_t* len, std::vector
 }
 
 void plan_decode_shared(const PlanParams& p, int32_t min_share_blk, int32_t group_wg_per_cu, int32_t tile_members,
-                        int32_t B, const int32_t* len, const int32_t* row_off, const int32_t* block_ids,
-                        SharedPlan& out) {
+                        int32_t prefix_align, int32_t B, const int32_t* len, const int32_t* row_off,
+                        const int32_t* block_ids, SharedPlan& out) {
   const size_t nB = static_cast<size_t>(B);
   out.group_leader.clear();
   out.group_prefix.clear();
@@ -78,7 +78,8 @@ void plan_decode_shared(const PlanParams& p, int32_t min_share_blk, int32_t grou
     const int32_t* rb = block_ids + row_off[b];
     int32_t n = 0;
     while (n < cap && ra[n] == rb[n]) ++n;
-    if (n < min_share_blk) continue;
+    n = n / prefix_align * prefix_align;      // shared prefixes end where the private blocks' kernel may start
+    if (n < min_share_blk || n < 1) continue;
     leader[b] = a;
     lcp[b] = n;
     min_lcp[a] = n_joined[a] == 0 ? n : std::min(min_lcp[a], n);

@@ -152,17 +152,21 @@ def test_grpo_workload_sampled():
     assert np.abs(out - out2).max() < 2e-2
 
 
-def test_other_head_groups_decode_without_sharing():
-    """5 query heads per kv head: the private blocks would need the packed-dot kernel, which is not
-    built for it; the call is then plain decode (bit for bit) and the plan reports no group."""
-    lens = [16 * 20 + 5] * 6 + [700]
-    c = shared_case(21, lens, [0] * 6 + [-1], [20], n_q=10, n_kv=2)
-    dc = DeviceCase(c)
-    plan = dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])
-    assert plan["n_groups"] == 0
-    out, lse = run_shared(dc)
-    plain, plain_lse = DeviceCase(c).decode()
-    assert np.array_equal(out, plain) and np.array_equal(lse, plain_lse)
+@pytest.mark.parametrize("n_q,n_kv", [(6, 2), (10, 2), (40, 8), (14, 2), (12, 1)])
+def test_groups_with_other_head_groups(n_q, n_kv):
+    """3, 5, 6, 7 and 12 query heads per kv head (40/8: Qwen3-14B): the shared prefix runs on the 128-row
+    matrix-core kernel, the private blocks on the one for short-row tiles, which starts at multiples of
+    4 blocks: prefixes of 21 and 7 blocks are shared as 20 and 4."""
+    lens = [16 * 21 + 5, 16 * 21 + 300, 16 * 40, 16 * 21 + 1, 2000,        # group 0: 21 common blocks
+            16 * 7 + 9, 16 * 7 + 100, 16 * 9,                              # group 1: 7 common blocks
+            700, 33]                                                        # nobody's
+    group_of = [0] * 5 + [1] * 3 + [-1, -1]
+    c = shared_case(22, lens, group_of, [21, 7], n_q=n_q, n_kv=n_kv)
     ref, ref_lse, spread = oracle_decode(c)
-    assert_close(out, ref, "G = 5 shared call", spread)
-    assert_lse_close(lse, ref_lse, "G = 5 shared call lse")
+    for kw in (dict(), dict(n_cu=8, wg_per_cu=2, min_chunk_blk=4, group_wg_per_cu=2, max_split=8)):
+        dc = DeviceCase(c, **kw)
+        plan = dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])
+        assert plan["n_groups"] == 2 and sorted(plan["group_prefix"].tolist()) == [4, 20]
+        out, lse = run_shared(dc)
+        assert_close(out, ref, f"shared, {n_q}/{n_kv} {kw}", spread)
+        assert_lse_close(lse, ref_lse, f"shared lse, {n_q}/{n_kv} {kw}")

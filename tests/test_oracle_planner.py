@@ -277,6 +277,14 @@ def test_shared_plan_invariants_random():
         plan = op.plan_decode_shared(lens, row_off, ids, **prm)
         check_shared_invariants(lens, row_off, ids, plan, prm["tile_members"], prm["tile_blk"], prm["max_split"],
                                 prm["min_share_blk"])
+        # prefixes that must end at multiples of 4 blocks (a kernel that starts at multiples of 64 keys reads
+        # the private blocks): still a valid plan, every prefix a multiple of 4, and with tile_blk = 4
+        # every private item starts at a multiple of 4.  (A prefix may come out longer than without the
+        # constraint: a member that shared fewer than 4 blocks no longer joins and no longer shortens it.)
+        prm4 = dict(prm, tile_blk=4, prefix_align=4)
+        plan4 = op.plan_decode_shared(lens, row_off, ids, **prm4)
+        check_shared_invariants(lens, row_off, ids, plan4, prm["tile_members"], 4, prm["max_split"], prm["min_share_blk"])
+        assert (plan4["group_prefix"] % 4 == 0).all() and (plan4["item_blk_begin"] % 4 == 0).all()
 
 
 def test_shared_plan_without_sharing_is_the_plain_plan():
@@ -381,3 +389,33 @@ def test_append_split_spreads_stragglers_only():
     plan = op.plan_append([120000], [8], 32)
     sp = op.split_append_tiles(plan, [120000], 8)
     assert sp["tile_nsplit"][0] >= 32           # one tile x 8 kv heads alone would use 8 of 512 slots
+
+
+def test_shared_plan_prefix_alignment_hand_example():
+    """Worked by hand.  Tables (block ids): trajectories 0-2 begin with the same 21 blocks 100..120,
+    trajectory 3 with the first 3 of them only, trajectories 4-5 with the same 7 blocks 200..206; every
+    length leaves those blocks wholly before the step's own row.  With prefix_align = 4 the common
+    prefixes 21 and 7 are used as 20 and 4; trajectory 3 (3 common blocks -> 0) stays alone, and with it
+    out of the way group 0's prefix is 20 (without alignment its lcp of 3 < min_share_blk = 4 would have
+    kept it out as well, and the prefix would be 21)."""
+    def own(n, base):
+        return list(range(base, base + n))
+    tables = [own(21, 100) + own(2, 1000), own(21, 100) + own(9, 1100), own(21, 100) + own(1, 1200),
+              own(3, 100) + own(30, 1300), own(7, 200) + own(1, 1400), own(7, 200) + own(5, 1500)]
+    lens = [16 * 22 + 3, 16 * 29 + 16, 16 * 21 + 1, 16 * 32 + 7, 16 * 7 + 2, 16 * 11 + 9]
+    row_off, ids = csr(tables)
+    free = op.plan_decode_shared(lens, row_off, ids, 2, 25, n_cu=4, wg_per_cu=2)
+    assert free["group_prefix"].tolist() == [21, 7] and free["traj_prefix"].tolist() == [21, 21, 21, 0, 7, 7]
+    plan = op.plan_decode_shared(lens, row_off, ids, 2, 25, n_cu=4, wg_per_cu=2, prefix_align=4)
+    assert plan["n_groups"] == 2 and plan["group_prefix"].tolist() == [20, 4]
+    assert plan["traj_prefix"].tolist() == [20, 20, 20, 0, 4, 4]
+    assert plan["members"].tolist() == [0, 1, 2, 4, 5]
+    # private work W = (23-20) + (30-20) + (22-20) + 33 + (8-4) + (12-4) = 60 blocks; target = 4*2/2 = 4;
+    # chunk = max(ceil(60/4), 16) = 16; trajectory 3 (33 blocks): ns = 3, per = ceil(33/3) = 11 -> 12,
+    # parts [0,12) [12,24) [24,33); everybody else one private part starting at the prefix
+    assert plan["chunk"] == 16
+    t3 = [(int(lo), int(hi)) for b, lo, hi in zip(plan["item_b"], plan["item_blk_begin"], plan["item_blk_end"]) if b == 3]
+    assert sorted(t3) == [(0, 12), (12, 24), (24, 33)]
+    starts = {int(b): int(lo) for b, lo in zip(plan["item_b"], plan["item_blk_begin"]) if b != 3}
+    assert starts == {0: 20, 1: 20, 2: 20, 4: 4, 5: 4}
+    check_shared_invariants(lens, row_off, ids, plan, 25, 4, 64, 4)

@@ -109,7 +109,8 @@ def test_random_append(seed):
 @pytest.mark.parametrize("seed", range(max(8, EXTRA)))
 def test_random_shared_decode(seed):
     rng = np.random.default_rng([103, seed])
-    n_q, n_kv, d = [(8, 2, 128), (4, 1, 128), (16, 2, 128), (32, 8, 128), (2, 2, 128)][int(rng.integers(0, 5))]
+    n_q, n_kv, d = [(8, 2, 128), (4, 1, 128), (16, 2, 128), (32, 8, 128), (2, 2, 128), (10, 2, 128), (40, 8, 128),
+                    (6, 2, 128)][int(rng.integers(0, 8))]
     n_groups = int(rng.integers(1, 5))
     group_of, lens, shared = [], [], []
     for g in range(n_groups):
