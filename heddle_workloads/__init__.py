@@ -284,7 +284,7 @@ def build_case(
 
 
 def make_workload(cfg_id: int, seed: int = 0, *, threads: int = 8, **kw):
-    """One of the five named workloads, generator = default_rng([cfg_id, seed]);
+    """One of the named workloads, generator = default_rng([cfg_id, seed]);
     draw order: lengths, chunk lengths, block permutation, Q, chunk K/V, pool."""
     w = WORKLOADS[cfg_id]
     rng = np.random.default_rng([cfg_id, seed])
