@@ -1,6 +1,7 @@
 // C ABI of libheddle: context, argument validation, plan upload, kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -997,11 +998,9 @@ static int kv_move(heddle_ctx* ctx, bool pack, int32_t n, const int32_t* block_i
   for (int32_t i = 0; i < n; ++i)
     if (block_ids_host[i] < 0 || block_ids_host[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
   if (!pack) {   // two staged blocks must not land in the same pool block
-    std::vector<uint8_t> seen(static_cast<size_t>(ctx->cfg.n_blocks), 0);
-    for (int32_t i = 0; i < n; ++i) {
-      if (seen[block_ids_host[i]]) return HEDDLE_E_INVAL;
-      seen[block_ids_host[i]] = 1;
-    }
+    std::vector<int32_t> sorted(block_ids_host, block_ids_host + n);
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return HEDDLE_E_INVAL;
   }
   if (!ctx->has_device || block_bytes % 4096 != 0) return HEDDLE_E_UNSUPPORTED;
   if (n == 0) return HEDDLE_OK;
