@@ -157,14 +157,23 @@ def _i32(a):
     return a, a.ctypes.data_as(i32p)
 
 
-def _dptr(t):
-    """Device pointer of a torch tensor (or a raw integer address / None)."""
+def _dptr(t, what="tensor", itemsize=None, min_elems=0):
+    """Device pointer of a torch tensor (or a raw integer address / None).  The C ABI takes plain
+    pointers and cannot see what is behind them, so a tensor is checked here: it must live on a
+    GPU, be contiguous, have elements of `itemsize` bytes and hold at least `min_elems` of them --
+    a host tensor or a short one would otherwise end in a GPU memory fault, not in an error."""
     if t is None:
         return None
     if isinstance(t, int):
         return t
+    if not t.is_cuda:
+        raise ValueError(f"{what}: expected a device tensor, got one on {t.device}")
     if not t.is_contiguous():
-        raise ValueError("device tensors must be contiguous")
+        raise ValueError(f"{what}: device tensors must be contiguous")
+    if itemsize is not None and t.element_size() != itemsize:
+        raise ValueError(f"{what}: elements of {itemsize} bytes expected, got {t.dtype}")
+    if t.numel() < min_elems:
+        raise ValueError(f"{what}: {t.numel()} elements, the call reads or writes {min_elems}")
     return t.data_ptr()
 
 
@@ -232,7 +241,9 @@ class Context:
     def __init__(self, n_q_heads, n_kv_heads, head_dim, n_blocks, kv_pool=None, device=-1, *,
                  n_cu=0, wg_per_cu=0, min_chunk_blk=0, tile_blk=0, max_split=0, scale=0.0,
                  min_share_blk=0, group_wg_per_cu=0, append_wg_per_cu=0, append_min_steps=0):
-        self.cfg = Config(n_q_heads, n_kv_heads, head_dim, 16, n_blocks, device, _dptr(kv_pool),
+        self.n_q_heads, self.n_kv_heads, self.head_dim, self.n_blocks = n_q_heads, n_kv_heads, head_dim, n_blocks
+        pool_elems = int(n_blocks) * int(n_kv_heads) * 2 * 16 * int(head_dim)
+        self.cfg = Config(n_q_heads, n_kv_heads, head_dim, 16, n_blocks, device, _dptr(kv_pool, "kv_pool", 2, pool_elems),
                           n_cu, wg_per_cu, min_chunk_blk, tile_blk, max_split, scale,
                           min_share_blk, group_wg_per_cu, append_wg_per_cu, append_min_steps)
         self._pool = kv_pool  # keep the tensor alive
@@ -346,17 +357,27 @@ class Context:
                     v_new=None, stream=None) -> None:
         lens_a, lens_p = _i32(lens)
         ro_a, ro_p = _i32(row_off_host)
-        args = DecodeArgs(lens_a.shape[0], lens_p, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
-                          _dptr(k_new), _dptr(v_new), _dptr(out), _dptr(lse))
+        args = self._decode_args(lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new)
         _check(lib.heddle_attn_decode(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_decode")
+
+    def _decode_args(self, lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new):
+        B = lens_a.shape[0]
+        if ro_a.shape[0] != B + 1:
+            raise ValueError("row_off_host must have one more entry than lens")
+        nq, nkv = B * self.n_q_heads * self.head_dim, B * self.n_kv_heads * self.head_dim
+        return DecodeArgs(B, lens_p, ro_p, _dptr(row_off, "row_off", 4, B + 1),
+                          _dptr(block_ids, "block_ids", 4, max(int(ro_a[-1]), 0)), _dptr(q, "q", 2, nq),
+                          _dptr(k_new, "k_new", 2, nkv), _dptr(v_new, "v_new", 2, nkv), _dptr(out, "out", 2, nq),
+                          _dptr(lse, "lse", 4, B * self.n_q_heads))
 
     def attn_decode_shared(self, lens, row_off_host, block_ids_host, row_off, block_ids, q, out, lse=None,
                            k_new=None, v_new=None, stream=None) -> None:
         lens_a, lens_p = _i32(lens)
         ro_a, ro_p = _i32(row_off_host)
         ids_a, ids_p = _i32(block_ids_host)
-        args = DecodeArgs(lens_a.shape[0], lens_p, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
-                          _dptr(k_new), _dptr(v_new), _dptr(out), _dptr(lse))
+        if ro_a.shape[0] and ids_a.shape[0] < int(ro_a[-1]):
+            raise ValueError("block_ids_host is shorter than the table row_off_host describes")
+        args = self._decode_args(lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new)
         _check(lib.heddle_attn_decode_shared(self._h, C.byref(args), ids_p, _stream_ptr(stream)),
                "heddle_attn_decode_shared")
 
@@ -365,18 +386,29 @@ class Context:
         L, Lp = _i32(ctx_lens)
         cu, cup = _i32(cu_chunk)
         ro_a, ro_p = _i32(row_off_host)
-        args = AppendArgs(L.shape[0], Lp, cup, ro_p, _dptr(row_off), _dptr(block_ids), _dptr(q),
-                          _dptr(k), _dptr(v), _dptr(out), _dptr(lse))
+        B = L.shape[0]
+        if cu.shape[0] != B + 1 or ro_a.shape[0] != B + 1:
+            raise ValueError("cu_chunk and row_off_host must have one more entry than ctx_lens")
+        rows = max(int(cu[-1]), 0)
+        nq, nkv = rows * self.n_q_heads * self.head_dim, rows * self.n_kv_heads * self.head_dim
+        args = AppendArgs(B, Lp, cup, ro_p, _dptr(row_off, "row_off", 4, B + 1),
+                          _dptr(block_ids, "block_ids", 4, max(int(ro_a[-1]), 0)), _dptr(q, "q", 2, nq),
+                          _dptr(k, "k", 2, nkv), _dptr(v, "v", 2, nkv), _dptr(out, "out", 2, nq),
+                          _dptr(lse, "lse", 4, rows * self.n_q_heads))
         _check(lib.heddle_attn_append(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_append")
 
     # ---- pack / unpack
     def kv_pack(self, block_ids, staging, stream=None) -> None:
         a, p = _i32(block_ids)
-        _check(lib.heddle_kv_pack(self._h, a.shape[0], p, _dptr(staging), _stream_ptr(stream)), "heddle_kv_pack")
+        need = a.shape[0] * self.n_kv_heads * 2 * 16 * self.head_dim
+        _check(lib.heddle_kv_pack(self._h, a.shape[0], p, _dptr(staging, "staging", 2, need), _stream_ptr(stream)),
+               "heddle_kv_pack")
 
     def kv_unpack(self, block_ids, staging, stream=None) -> None:
         a, p = _i32(block_ids)
-        _check(lib.heddle_kv_unpack(self._h, a.shape[0], p, _dptr(staging), _stream_ptr(stream)), "heddle_kv_unpack")
+        need = a.shape[0] * self.n_kv_heads * 2 * 16 * self.head_dim
+        _check(lib.heddle_kv_unpack(self._h, a.shape[0], p, _dptr(staging, "staging", 2, need), _stream_ptr(stream)),
+               "heddle_kv_unpack")
 
     # ---- measurement
     def timing_enable(self, every: int = 1) -> None:

@@ -311,10 +311,36 @@ def test_ragged_lengths_other_head_groups(n_q, n_kv):
 def test_head_shapes_no_kernel_is_built_for_are_refused():
     import paper_2603_28101_amd as heddle
     torch = __import__("torch")
-    pool = torch.zeros((4, 2, 2, 16 * 64), dtype=torch.bfloat16, device="cuda")
+    pool = torch.zeros((4, 2, 2, 16 * 128), dtype=torch.bfloat16, device="cuda")
     for n_q, n_kv, d, kw in ((6, 2, 64, {}),                    # 3 heads per kv head at d = 64
                              (10, 2, 128, dict(tile_blk=2)),    # parts that would not start at multiples of 64 keys
                              (66, 2, 128, {})):                 # 33 heads per kv head
         with pytest.raises(heddle.HeddleError) as e:
             heddle.Context(n_q, n_kv, d, 4, kv_pool=pool, device=0, **kw)
         assert e.value.code == heddle.E_UNSUPPORTED, (n_q, n_kv, d)
+
+
+def test_binding_refuses_tensors_that_would_fault():
+    """The C ABI sees plain pointers; the Python binding checks what is behind them before the call:
+    a host tensor, a tensor of the wrong element size or one that is too short raises there."""
+    torch = __import__("torch")
+    c = small(33, [40, 9], 8, 2, 128)
+    dc = DeviceCase(c)
+    good, _ = dc.decode()
+    cases = {
+        "q on the host": dict(q=dc.q.cpu()),
+        "out too short": dict(out=dc.out[:1]),
+        "q in float32": dict(q=dc.q.float()),
+        "lse too short": dict(lse=dc.lse[:1, :4].contiguous()),
+        "block ids too short": dict(block_ids=dc.block_ids[:2]),
+    }
+    for what, kw in cases.items():
+        a = dict(row_off=dc.row_off, block_ids=dc.block_ids, q=dc.q, out=dc.out, lse=dc.lse)
+        a.update(kw)
+        with pytest.raises(ValueError):
+            dc.ctx.attn_decode(c["lens"], c["row_off"], a["row_off"], a["block_ids"], a["q"], a["out"], a["lse"])
+    with pytest.raises(ValueError):
+        import paper_2603_28101_amd as heddle
+        heddle.Context(8, 2, 128, c["n_blocks"] + 1, kv_pool=dc.pool, device=0)      # pool smaller than n_blocks says
+    again, _ = dc.decode()
+    assert np.array_equal(good, again)
