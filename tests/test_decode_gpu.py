@@ -344,3 +344,37 @@ def test_binding_refuses_tensors_that_would_fault():
         heddle.Context(8, 2, 128, c["n_blocks"] + 1, kv_pool=dc.pool, device=0)      # pool smaller than n_blocks says
     again, _ = dc.decode()
     assert np.array_equal(good, again)
+
+
+def test_many_queued_calls_with_different_plans():
+    """Forty decode calls with forty different batches are issued behind several milliseconds of other work on
+    the same stream, so that the host runs far ahead of the device and goes round the ring of pinned
+    plan buffers five times; every call must still run with its own plan (a buffer handed out again
+    before its copy kernel has read it would show as a wrong result)."""
+    import paper_2603_28101_amd as heddle
+    torch = __import__("torch")
+    rng = np.random.default_rng(77)
+    lens_all = [np.concatenate([rng.integers(1, 600, int(rng.integers(2, 9))), [int(rng.integers(1500, 5000))]])
+                for _ in range(40)]
+    B_max, longest = 9, 5000
+    # one pool and table for all calls: every call uses the first B trajectories at its own lengths
+    c = small(34, [longest] * B_max, 8, 2, 128)
+    dc = DeviceCase(c)
+    outs = [torch.full((B_max, 8, 128), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in lens_all]
+    lses = [torch.full((B_max, 8), float("nan"), dtype=torch.float32, device="cuda") for _ in lens_all]
+    busy = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    dc.decode()                                    # scratch of the largest size first
+    torch.cuda.synchronize()
+    for _ in range(200):                           # ~8 ms of reads in front of the calls
+        heddle.stream_read(busy, busy.numel(), sink)
+    for lens, out, lse in zip(lens_all, outs, lses):
+        B = len(lens)
+        dc.ctx.attn_decode(lens, c["row_off"][: B + 1], dc.row_off, dc.block_ids, dc.q, out, lse)
+    torch.cuda.synchronize()
+    for i, (lens, out, lse) in enumerate(zip(lens_all, outs, lses)):
+        B = len(lens)
+        ref, ref_lse, spread = oa.decode(c["pool"], c["row_off"][: B + 1], c["block_ids"], lens, c["q"][:B], 2,
+                                         with_spread=True)
+        assert_close(bits_to_f64(bf16_to_host_bits(out))[:B], ref, f"queued call {i}", spread)
+        assert_lse_close(lse.cpu().numpy()[:B], ref_lse, f"queued call {i} lse")
