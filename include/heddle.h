@@ -103,11 +103,17 @@ int heddle_ctx_destroy(heddle_ctx* ctx);
  * A trajectory's blocks stay allocated across tool calls and preemption
  * (Sec. 4.2) and are returned when it finishes.  Stack discipline: a fresh
  * context hands out 0,1,2,...; free pushes ids in the order given; alloc pops,
- * most recently freed first.
- *   alloc: n < 0 -> INVAL; fewer than n free -> NOMEM; nothing changes on error.
- *   free:  any id out of range, not allocated, or repeated in the call -> INVAL,
- *          nothing changes. */
+ * most recently freed first.  A block may have several holders: the samples
+ * of one prompt (Sec. 7, "Workloads") name the prompt's blocks in their tables
+ * (what heddle_attn_decode_shared reads once per group).  alloc gives a block
+ * one holder, retain adds one, free takes one away; the block goes back on
+ * the stack when its last holder frees it, in the order of that free call.
+ *   alloc:  n < 0 -> INVAL; fewer than n free -> NOMEM; nothing changes on error.
+ *   retain: any id out of range, not allocated, or repeated in the call -> INVAL,
+ *           nothing changes.
+ *   free:   the same conditions -> INVAL, nothing changes. */
 int heddle_kv_alloc(heddle_ctx* ctx, int32_t n, int32_t* out_block_ids /* HOST [n] */);
+int heddle_kv_retain(heddle_ctx* ctx, int32_t n, const int32_t* block_ids /* HOST [n] */);
 int heddle_kv_free(heddle_ctx* ctx, int32_t n, const int32_t* block_ids /* HOST [n] */);
 int heddle_kv_num_free(const heddle_ctx* ctx, int32_t* out);
 

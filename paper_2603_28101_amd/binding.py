@@ -108,6 +108,7 @@ lib.heddle_ctx_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
 lib.heddle_ctx_destroy.argtypes = [vp]
 lib.heddle_kv_alloc.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_free.argtypes = [vp, C.c_int32, i32p]
+lib.heddle_kv_retain.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_num_free.argtypes = [vp, i32p]
 lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
@@ -131,7 +132,7 @@ lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
-for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free",
+for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free", "heddle_kv_retain",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
            "heddle_timing_read", "heddle_timing_samples", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
@@ -267,6 +268,10 @@ class Context:
         out = np.empty(max(n, 0), dtype=np.int32)
         _check(lib.heddle_kv_alloc(self._h, n, out.ctypes.data_as(i32p)), "heddle_kv_alloc")
         return out
+
+    def kv_retain(self, ids) -> None:
+        a, p = _i32(ids)
+        _check(lib.heddle_kv_retain(self._h, a.shape[0], p), "heddle_kv_retain")
 
     def kv_free(self, ids) -> None:
         a, p = _i32(ids)

@@ -295,6 +295,11 @@ int heddle_kv_alloc(heddle_ctx* ctx, int32_t n, int32_t* out_block_ids) {
   return ctx->blocks->alloc(n, out_block_ids);
 }
 
+int heddle_kv_retain(heddle_ctx* ctx, int32_t n, const int32_t* block_ids) {
+  if (ctx == nullptr) return HEDDLE_E_INVAL;
+  return ctx->blocks->retain(n, block_ids);
+}
+
 int heddle_kv_free(heddle_ctx* ctx, int32_t n, const int32_t* block_ids) {
   if (ctx == nullptr) return HEDDLE_E_INVAL;
   return ctx->blocks->release(n, block_ids);

@@ -15,13 +15,17 @@ class BlockManager {
  public:
   explicit BlockManager(int32_t n_blocks);
   int alloc(int32_t n, int32_t* out);
+  int retain(int32_t n, const int32_t* ids);
   int release(int32_t n, const int32_t* ids);
   int32_t num_free() const { return static_cast<int32_t>(stack_.size()); }
 
  private:
   enum : uint8_t { kFree = 0, kHeld = 1, kMarked = 2 };
-  std::vector<int32_t> stack_;  // top = back
+  // Validates a list (every id in range, held, named once) by marking; restores the marks.
+  bool valid_held_list(int32_t n, const int32_t* ids);
+  std::vector<int32_t> stack_;    // top = back
   std::vector<uint8_t> state_;
+  std::vector<int32_t> holders_;  // per block: trajectories that name it (0 = free)
 };
 
 // ---------------------------------------------------------------- planners

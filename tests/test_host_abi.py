@@ -66,12 +66,13 @@ def test_manager_golden_traces_on_library():
                     with pytest.raises(heddle.HeddleError) as e:
                         c.kv_alloc(o[1])
                     assert e.value.code == o[2], o
-            elif o[0] == "free":
+            elif o[0] in ("free", "retain"):
+                call = c.kv_free if o[0] == "free" else c.kv_retain
                 if o[2] == 0:
-                    c.kv_free(o[1])
+                    call(o[1])
                 else:
                     with pytest.raises(heddle.HeddleError) as e:
-                        c.kv_free(o[1])
+                        call(o[1])
                     assert e.value.code == o[2], o
             else:
                 assert c.kv_num_free() == o[1], o
@@ -95,16 +96,19 @@ def test_manager_random_scripts_match_oracle():
                 except heddle.HeddleError as e:
                     assert e.code == code != 0
             elif r < 0.9 and held:
-                k = int(rng.integers(1, len(held) + 1))
-                idx = rng.permutation(len(held))[:k].tolist()
-                ids = [held[i] for i in idx]
+                distinct = sorted(set(held))
+                k = int(rng.integers(1, len(distinct) + 1))
+                idx = rng.permutation(len(distinct))[:k].tolist()
+                ids = [distinct[i] for i in idx]
                 if rng.random() < 0.15:          # corrupt: duplicate / foreign / out of range
                     ids = ids + [ids[0]] if rng.random() < 0.5 else ids + [int(rng.integers(-3, n + 3))]
-                code = m.free(ids)
+                retain = rng.random() < 0.3      # one more holder, or one fewer
+                code = m.retain(ids) if retain else m.free(ids)
                 try:
-                    c.kv_free(ids)
+                    (c.kv_retain if retain else c.kv_free)(ids)
                     assert code == 0
-                    held = [h for h in held if h not in set(ids)]
+                    for i in ids:                # `held` lists a block once per holder
+                        held.append(i) if retain else held.remove(i)
                 except heddle.HeddleError as e:
                     assert e.code == code != 0
             assert c.kv_num_free() == m.num_free()

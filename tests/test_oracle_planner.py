@@ -140,6 +140,8 @@ def replay(trace):
             assert (code, ids) == (op_[2], op_[3]), op_
         elif op_[0] == "free":
             assert m.free(op_[1]) == op_[2], op_
+        elif op_[0] == "retain":
+            assert m.retain(op_[1]) == op_[2], op_
         else:
             assert m.num_free() == op_[1], op_
 
@@ -174,6 +176,43 @@ def test_manager_conservation_random():
             assert got == [ids[-1]]
             held += got
         assert m.num_free() + len(held) == 50
+
+
+def test_manager_holders_random():
+    """With retain in the mix: a block is on the stack exactly when nobody holds it, and a block comes
+    back when as many frees as (1 + retains) have named it."""
+    rng = np.random.default_rng(3)
+    m = KVManager(40)
+    count = {}                                   # block -> holders, kept here independently
+    for _ in range(3000):
+        r = rng.random()
+        if r < 0.4:
+            code, ids = m.alloc(int(rng.integers(0, 6)))
+            if code == 0:
+                for i in ids:
+                    assert i not in count
+                    count[i] = 1
+        elif count:
+            held = sorted(count)
+            k = int(rng.integers(1, len(held) + 1))
+            ids = [held[i] for i in rng.permutation(len(held))[:k]]
+            if r < 0.6:
+                assert m.retain(ids) == 0
+                for i in ids:
+                    count[i] += 1
+            else:
+                assert m.free(ids) == 0
+                back = [i for i in ids if count[i] == 1]
+                for i in ids:
+                    count[i] -= 1
+                    if count[i] == 0:
+                        del count[i]
+                if back:                         # the last block that lost its last holder is on top
+                    code, got = m.alloc(1)
+                    assert code == 0 and got == [back[-1]]
+                    count[got[0]] = 1
+        assert m.num_free() + len(count) == 40
+        assert all(m.is_free[i] == (i not in count) for i in range(40))
 
 
 # ---------------------------------------------------------------- shared-prefix decode plan

@@ -130,6 +130,8 @@ def test_rollout_of_six_trajectories():
         for b in members:
             w.tables[b] = list(w.tables[leader][:whole])
             w.lens[b] = whole * 16
+            w.ctx.kv_retain(np.asarray(w.tables[b], dtype=np.int32))      # one more holder of the prompt's blocks
+            assert w.ref_blocks.retain(w.tables[b]) == 0
     tail = [w.lens[0] - (w.lens[0] // 16) * 16, w.lens[3] - (w.lens[3] // 16) * 16]     # 8 and 11 tokens
     # re-append those tail tokens for the members (in a real rollout: a copy; here fresh rows)
     w.append([1, 2, 4, 5], [tail[0], tail[0], tail[1], tail[1]], "prompt tails of the other samples")
@@ -144,10 +146,11 @@ def test_rollout_of_six_trajectories():
     for step in range(2):
         w.decode([5, 2, 0, 4], f"decode step {step}")
 
-    # 5. trajectory 1 is preempted: packed, its private blocks freed ...
+    # 5. trajectory 1 is preempted: its private blocks packed, its whole table freed; the prompt's
+    #    blocks stay allocated, samples 0 and 2 still hold them ...
     b = 1
     n_blk = -(-w.lens[b] // 16)
-    shared_blk = prompts[0] // 16                       # the prompt's whole blocks stay with samples 0 and 2
+    shared_blk = prompts[0] // 16
     private = w.tables[b][shared_blk:n_blk]
     staging = torch.empty((len(private), N_KV * 2 * 16 * D), dtype=torch.bfloat16, device="cuda")
     w.ctx.kv_pack(np.asarray(private, dtype=np.int32), staging)
@@ -155,21 +158,31 @@ def test_rollout_of_six_trajectories():
     row_off, ids = w.csr([b])
     staged_ref = oa.pack(w.ref_pool, row_off, ids, 0, w.lens[b])[shared_blk:]
     assert np.array_equal(bf16_to_host_bits(staging).reshape(staged_ref.shape), staged_ref)
-    w.ctx.kv_free(np.asarray(w.tables[b][shared_blk:], dtype=np.int32))
-    assert w.ref_blocks.free(w.tables[b][shared_blk:]) == 0
-    w.tables[b] = w.tables[b][:shared_blk]
+    free_before = w.ctx.kv_num_free()
+    w.ctx.kv_free(np.asarray(w.tables[b], dtype=np.int32))
+    assert w.ref_blocks.free(w.tables[b]) == 0
+    assert w.ctx.kv_num_free() == free_before + len(w.tables[b]) - shared_blk
+    prompt_blocks = w.tables[b][:shared_blk]
+    w.tables[b] = []
     # ... which the next tool output of trajectory 3 takes (most recently freed first)
     w.append([3], [300], "tool output into recycled blocks")
-    # 6. trajectory 1 comes back under new blocks
+    # 6. trajectory 1 comes back: it holds the prompt's blocks again and gets new private ones
+    w.ctx.kv_retain(np.asarray(prompt_blocks, dtype=np.int32))
+    assert w.ref_blocks.retain(prompt_blocks) == 0
     got = w.ctx.kv_alloc(len(private))
     code, ref_ids = w.ref_blocks.alloc(len(private))
     assert code == 0 and got.tolist() == ref_ids
     w.ctx.kv_unpack(got, staging)
     torch.cuda.synchronize()
     oa.unpack(w.ref_pool, got, staged_ref)
-    w.tables[b] += got.tolist()
+    w.tables[b] = prompt_blocks + got.tolist()
     w.check_pool("unpack")
     # 7. everybody decodes again, shared path, then plain
     w.decode([0, 1, 2, 3, 4, 5], "shared decode after resume", shared=True)
     w.decode([0, 1, 2, 3, 4, 5], "decode after resume")
     assert w.ctx.kv_num_free() == w.ref_blocks.num_free()
+    # 8. everybody finishes: each frees its whole table, shared blocks return with their last holder
+    for b in range(6):
+        w.ctx.kv_free(np.asarray(w.tables[b], dtype=np.int32))
+        assert w.ref_blocks.free(w.tables[b]) == 0
+    assert w.ctx.kv_num_free() == N_BLOCKS == w.ref_blocks.num_free()
