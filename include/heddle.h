@@ -98,6 +98,13 @@ typedef struct heddle_config {
 int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out);
 /* Synchronises the device if the context has enqueued work, frees everything it owns. */
 int heddle_ctx_destroy(heddle_ctx* ctx);
+/* Points the context at another pool of the same shape (n_blocks, n_kv_heads,
+ * head_dim, layout above): DEVICE, caller-owned.  A model keeps one pool per
+ * layer while block table, lengths and block manager are common to all layers
+ * (a token has the same position in each), so one context serves them in turn.
+ * Calls already enqueued keep the pool they were issued with.  NULL or a
+ * host-only context -> INVAL. */
+int heddle_ctx_set_kv_pool(heddle_ctx* ctx, void* kv_pool);
 
 /* ---- block manager of the paged pool (host only, O(n), all-or-nothing) ----
  * A trajectory's blocks stay allocated across tool calls and preemption

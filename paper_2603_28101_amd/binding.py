@@ -109,6 +109,7 @@ lib.heddle_ctx_destroy.argtypes = [vp]
 lib.heddle_kv_alloc.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_free.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_retain.argtypes = [vp, C.c_int32, i32p]
+lib.heddle_ctx_set_kv_pool.argtypes = [vp, vp]
 lib.heddle_kv_num_free.argtypes = [vp, i32p]
 lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
@@ -132,7 +133,8 @@ lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
-for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_kv_alloc", "heddle_kv_free", "heddle_kv_retain",
+for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_set_kv_pool", "heddle_kv_alloc", "heddle_kv_free",
+           "heddle_kv_retain",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
            "heddle_timing_read", "heddle_timing_samples", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
@@ -262,6 +264,12 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_kv_pool(self, kv_pool) -> None:
+        """Another pool of the same shape (one per layer of a model); later calls read and write it."""
+        pool_elems = self.n_blocks * self.n_kv_heads * 2 * 16 * self.head_dim
+        _check(lib.heddle_ctx_set_kv_pool(self._h, _dptr(kv_pool, "kv_pool", 2, pool_elems)), "heddle_ctx_set_kv_pool")
+        self._pool = kv_pool  # keep the tensor alive
 
     # ---- block manager
     def kv_alloc(self, n: int) -> np.ndarray:

@@ -305,6 +305,12 @@ int heddle_kv_free(heddle_ctx* ctx, int32_t n, const int32_t* block_ids) {
   return ctx->blocks->release(n, block_ids);
 }
 
+int heddle_ctx_set_kv_pool(heddle_ctx* ctx, void* kv_pool) {
+  if (ctx == nullptr || kv_pool == nullptr || ctx->cfg.device < 0) return HEDDLE_E_INVAL;
+  ctx->cfg.kv_pool = kv_pool;
+  return HEDDLE_OK;
+}
+
 int heddle_kv_num_free(const heddle_ctx* ctx, int32_t* out) {
   if (ctx == nullptr || out == nullptr) return HEDDLE_E_INVAL;
   *out = ctx->blocks->num_free();

@@ -7,7 +7,7 @@ import pytest
 import heddle_workloads as hw
 from oracle import attention as oa
 from oracle import planner as op
-from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64,
+from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64, torch_mod,
                             bf16_to_host_bits)
 
 pytestmark = pytest.mark.gpu
@@ -378,3 +378,37 @@ def test_many_queued_calls_with_different_plans():
                                          with_spread=True)
         assert_close(bits_to_f64(bf16_to_host_bits(out))[:B], ref, f"queued call {i}", spread)
         assert_lse_close(lse.cpu().numpy()[:B], ref_lse, f"queued call {i} lse")
+
+
+def test_one_context_serves_a_pool_per_layer():
+    """The layers of a model share block table, lengths and block manager and keep a pool each.  Three
+    decode steps, each storing a new row, are queued without a wait in between, the context pointed at
+    layer 0, layer 1 and layer 0 again: every call reads and writes the pool it was issued with."""
+    torch = torch_mod()
+    lens = [1, 16, 17, 300, 64, 2100]
+    c = small(21, lens, 8, 2, 128)
+    host_pools = [c["pool"].copy(), c["pool"] ^ np.uint16(0x8000)]       # layer 1: every value negated
+    dc = DeviceCase(c)
+    dev_pools = [dc.pool, to_dev_bf16(host_pools[1])]
+    rng = np.random.default_rng(8)
+    calls = []
+    for layer in (0, 1, 0):
+        k_new = hw.f32_to_bf16_bits(rng.standard_normal((6, 2, 128), dtype=np.float32))
+        v_new = hw.f32_to_bf16_bits(rng.standard_normal((6, 2, 128), dtype=np.float32))
+        out = torch.full(c["q"].shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full(c["q"].shape[:2], float("nan"), dtype=torch.float32, device="cuda")
+        k_dev, v_dev = to_dev_bf16(k_new), to_dev_bf16(v_new)
+        dc.ctx.set_kv_pool(dev_pools[layer])
+        dc.ctx.attn_decode(c["lens"], c["row_off"], dc.row_off, dc.block_ids, dc.q, out, lse, k_dev, v_dev)
+        for b in range(6):
+            oa.write_kv(host_pools[layer], c["row_off"], c["block_ids"], [lens[b] - 1], b, k_new[b:b + 1],
+                        v_new[b:b + 1])
+        calls.append((layer, out, lse, k_dev, v_dev, oracle_decode(c, pool=host_pools[layer])))
+    torch.cuda.synchronize()
+    for i, (layer, out, lse, _, _, (ref, ref_lse, spread)) in enumerate(calls):
+        assert_close(bits_to_f64(bf16_to_host_bits(out)), ref, f"call {i} on layer {layer}", spread)
+        assert_lse_close(lse.cpu().numpy().astype(np.float64), ref_lse)
+    for layer in (0, 1):
+        assert np.array_equal(bf16_to_host_bits(dev_pools[layer]), host_pools[layer]), f"pool of layer {layer}"
+    with pytest.raises(Exception):
+        dc.ctx.set_kv_pool(torch.empty(16, dtype=torch.bfloat16, device="cuda"))       # too small for the context
