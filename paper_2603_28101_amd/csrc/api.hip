@@ -204,6 +204,21 @@ struct TimedScope {
   }
 };
 
+// Frees what the context holds on its device (the device must be current).
+void release_device_objects(heddle_ctx* ctx) {
+  for (StagingSlot& s : ctx->staging)
+    if (s.host) (void)hipHostFree(s.host);
+  for (UploadGuard& g : ctx->guards)
+    if (g.done) (void)hipEventDestroy(g.done);
+  if (ctx->dev_plan) (void)hipFree(ctx->dev_plan);
+  if (ctx->dev_part_acc) (void)hipFree(ctx->dev_part_acc);
+  if (ctx->dev_part_ml) (void)hipFree(ctx->dev_part_ml);
+  for (KernelTimer& t : ctx->timers) {
+    for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
+  }
+}
+
 bool table_covers(const int32_t* row_off_host, int32_t b, int64_t tokens) {
   const int64_t have = static_cast<int64_t>(row_off_host[b + 1]) - row_off_host[b];
   return have >= (tokens + HEDDLE_BLOCK_TOKENS - 1) / HEDDLE_BLOCK_TOKENS;
@@ -249,7 +264,14 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
     DeviceGuard guard(cfg->device);
     if (!guard.ok()) return HEDDLE_E_HIP;
     if (n_cu == 0) HEDDLE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, cfg->device));
-    for (UploadGuard& g : ctx->guards) HEDDLE_HIP(hipEventCreateWithFlags(&g.done, hipEventDisableTiming));
+    for (UploadGuard& g : ctx->guards) {
+      const hipError_t e = hipEventCreateWithFlags(&g.done, hipEventDisableTiming);
+      if (e != hipSuccess) {
+        g.done = nullptr;
+        release_device_objects(ctx.get());
+        return hip_failed(e, "hipEventCreateWithFlags", __LINE__);
+      }
+    }
     ctx->has_device = true;
   } else if (n_cu == 0) {
     n_cu = 256;
@@ -274,17 +296,7 @@ int heddle_ctx_destroy(heddle_ctx* ctx) {
   if (ctx->has_device) {
     DeviceGuard guard(ctx->cfg.device);
     if (ctx->enqueued && hipDeviceSynchronize() != hipSuccess) rc = HEDDLE_E_HIP;
-    for (StagingSlot& s : ctx->staging)
-      if (s.host) (void)hipHostFree(s.host);
-    for (UploadGuard& g : ctx->guards)
-      if (g.done) (void)hipEventDestroy(g.done);
-    if (ctx->dev_plan) (void)hipFree(ctx->dev_plan);
-    if (ctx->dev_part_acc) (void)hipFree(ctx->dev_part_acc);
-    if (ctx->dev_part_ml) (void)hipFree(ctx->dev_part_ml);
-    for (KernelTimer& t : ctx->timers) {
-      for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
-      for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
-    }
+    release_device_objects(ctx);
   }
   delete ctx;
   return rc;
@@ -1024,6 +1036,7 @@ static int kv_move(heddle_ctx* ctx, bool pack, int32_t n, const int32_t* block_i
   std::memcpy(slot->host, block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
   rc = upload(ctx, slot, static_cast<size_t>(n), stream);
   if (rc != HEDDLE_OK) return rc;
+  ctx->enqueued = true;
   TimedScope t(ctx, pack ? 4 : 5, stream);
   HEDDLE_HIP(launch_kv_move(pack, ctx->cfg.kv_pool, staging, ctx->dev_plan, n, block_bytes, stream));
   return HEDDLE_OK;
@@ -1047,10 +1060,14 @@ int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {
     HEDDLE_HIP(hipDeviceSynchronize());
     for (KernelTimer& t : ctx->timers) {
       while (t.start.size() < static_cast<size_t>(kEventPairs)) {
-        hipEvent_t a = nullptr, b = nullptr;
+        hipEvent_t a = nullptr, b = nullptr;          // a pair or nothing: the two lists stay the same length
         HEDDLE_HIP(hipEventCreate(&a));
+        const hipError_t e = hipEventCreate(&b);
+        if (e != hipSuccess) {
+          (void)hipEventDestroy(a);
+          return hip_failed(e, "hipEventCreate", __LINE__);
+        }
         t.start.push_back(a);
-        HEDDLE_HIP(hipEventCreate(&b));
         t.stop.push_back(b);
       }
       t.recorded = 0;
