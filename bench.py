@@ -235,6 +235,17 @@ def main():
         roofline["kernel_us_p10_p50_p90"] = [round(float(p10), 2), round(float(p50), 2), round(float(p90), 2)]
 
     extra = {}
+    if bound == "hbm":
+        roofline["frac_of_stream_read_ceiling"] = round(roofline["achieved"] / stream_gbps, 4)
+    if kind == "decode" and not shared:
+        # bytes the step moves besides K/V, left out of the rate (listed so that the omission can be judged)
+        plan = ctx.plan_decode(lens)
+        n_parts = int(plan["nsplit"][plan["nsplit"] > 1].sum())
+        n_blk = int(((np.asarray(lens, dtype=np.int64) + 15) // 16).sum())
+        extra["bytes_not_counted"] = {
+            "q_and_out": 2 * w.B * w.n_q_heads * w.head_dim * 2,
+            "block_table": 4 * n_blk * w.n_kv_heads,
+            "partials_written_and_read": 2 * n_parts * w.n_q_heads * (w.head_dim + 4) * 4}
     if kind == "decode" and shared:
         # the same batch through the plain decode entry point, which reads a shared block once per
         # trajectory that names it
