@@ -336,3 +336,22 @@ def test_append_split_matches_oracle():
             assert np.array_equal(got[k], plan[k]), k
         for k in ("tile_nsplit", "tile_part_base", "item_tile", "item_k", "item_step_begin", "item_step_end"):
             assert np.array_equal(got[k], ref[k]), (trial, k)
+
+
+def test_plain_c_client_compiles_links_and_runs(tmp_path):
+    """heddle.h is a C header: a C99 program (strict warnings) links against the library and gets the
+    hand-worked plan and the block ids the stack rule gives."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "c_abi_client")
+    libdir = os.path.dirname(heddle.lib_path())
+    cmd = [cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, "-L", libdir, "-lheddle",
+           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"]
+    built = subprocess.run(cmd, capture_output=True, text=True)
+    assert built.returncode == 0, built.stderr
+    ran = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert ran.returncode == 0 and ran.stdout.strip() == "ok", ran.stdout + ran.stderr
