@@ -69,8 +69,9 @@ typedef struct heddle_ctx heddle_ctx;
 typedef struct heddle_config {
   int32_t n_q_heads;      /* multiple of n_kv_heads; query heads per kv head G = n_q/n_kv: with head_dim
                              128 any G from 1 to 32 (decode for G other than 1, 2, 4, 8 needs tile_blk
-                             to be a multiple of 4; append needs head_dim 128); with head_dim 64
-                             G in {1,2,4,8}, decode only.  Else HEDDLE_E_UNSUPPORTED. */
+                             to be a multiple of 4); with head_dim 64 G in {1,2,4,8} (every call; chunks
+                             of a few rows run in the kernel for long chunks there).
+                             Else HEDDLE_E_UNSUPPORTED. */
   int32_t n_kv_heads;
   int32_t head_dim;       /* 64 or 128 */
   int32_t block_tokens;   /* must be 16 */
@@ -242,7 +243,7 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
  *  6. trajectory b: cut(nblk[b]-prefix[b], chunk) -> parts over [prefix[b] + k*per, ...)
  *     with slot = parts_g + k; nsplit[b] = parts_g + count; items sorted as before.
  * All arrays HOST, caller-owned; capacities too small -> NOMEM.  On a shape the
- * matrix-core kernel is not built for (head_dim != 128) no groups are formed. */
+ * matrix-core kernel is not built for (head_dim other than 64 and 128) no groups are formed. */
 typedef struct heddle_shared_plan {
   int32_t  cap_items, cap_gitems, cap_groups;          /* in  */
   int32_t  n_items, n_gitems, n_groups, chunk, chunk_g; /* out */

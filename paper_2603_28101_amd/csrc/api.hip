@@ -244,7 +244,7 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
   if (cfg->device >= 0) {
     const int32_t group = cfg->n_q_heads / cfg->n_kv_heads;
     const int32_t tile_blk = cfg->tile_blk ? cfg->tile_blk : 4;
-    const bool on_mfma_only = append_shape_supported(group, cfg->head_dim) &&
+    const bool on_mfma_only = narrow_shape_supported(group, cfg->head_dim) &&
                               tile_blk % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
     if (!decode_shape_supported(group, cfg->head_dim) && !on_mfma_only) return HEDDLE_E_UNSUPPORTED;
   }
@@ -904,7 +904,7 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   // -- unless they are the smaller part of the batch: a few short-row tiles next to a large append
   // would make a second launch that runs alone on a handful of compute units, while inside the
   // large launch they cost next to nothing
-  int32_t narrow_rows = narrow_tile_rows(G);
+  int32_t narrow_rows = narrow_shape_supported(G, D) ? narrow_tile_rows(G) : 0;
   size_t n_wide = 0;
   int64_t steps_wide = 0, steps_narrow = 0;
   for (const AppendItem& it : sp.items) {

@@ -62,7 +62,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // blocks they share (whole blocks, every key visible to every row), split-K partial output.
 template <int D, typename Launch>
 __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
-  static_assert(D == 128, "staging roles and swizzle are written for head_dim 128");
+  static_assert(D == 128 || D == 64, "staging roles and swizzle are written for head_dim 128 and 64");
   constexpr bool kGroup = std::is_same<Launch, GroupLaunch>::value;
   constexpr int NK = D / 16;             // MFMA steps over d for S^T
   constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
@@ -73,9 +73,9 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   constexpr int kStageV = kChunkBlocks * kTileElems;   // elements of V per LDS stage
   constexpr int kVPlane = D * 8;                       // elements of one 8-key plane of a V block
 
-  // Two stages (double buffer).  K rows are 256 B = 16 slots of 16 B; slot c of key row t is
-  // stored at slot c ^ (t & 15), so that the 32 lanes reading the same d-slice of 32
-  // different keys spread over all banks.  A V block is two planes of [d][8 keys]: plane 0
+  // Two stages (double buffer).  K rows are 2 D bytes = D/8 slots of 16 B (16 at d = 128); slot c of
+  // key row t is stored at slot c ^ (t & (D/8 - 1)), so that the 32 lanes reading the same d-slice
+  // of 32 different keys spread over the banks.  A V block is two planes of [d][8 keys]: plane 0
   // holds keys {0-3, 8-11}, plane 1 keys {4-7, 12-15}, so that the 16 lanes an LDS read serves
   // per cycle (consecutive head-dim rows of one plane) fall into 16 different bank groups;
   // with [d][16 keys] rows every other row of a half collided.
@@ -149,11 +149,18 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   const int n_blocks_needed = (extent + kBlockTokens - 1) / kBlockTokens;
   const int n_chunks = (extent + kChunkTokens - 1) / kChunkTokens;
 
-  // staging roles: per chunk and thread one 16-byte piece of K and one of V from each block
+  // staging roles.  d = 128: per chunk and thread one 16-byte piece of K and one of V from each block
   //   K piece x: key row 16x + tid/16, d slice tid%16
   //   V piece x: block x, d row tid/2, key half tid%2 (8 keys)
-  const int k_tok = tid >> 4, k_slice = tid & 15;
-  const int v_row = tid >> 1, v_half = tid & 1;
+  // d = 64: a block's K tile and V tile are 128 pieces each, so waves 0-1 stage K and waves 2-3
+  // stage V, one piece per thread and block
+  //   K piece x: key row 16x + (tid%128)/8, d slice tid%8
+  //   V piece x: block x, d row (tid%128)/2, key half tid%2
+  constexpr int kSlots = D / 8;                       // 16-byte pieces of a K row
+  const bool stages_v = D == 128 || tid >= 128;       // (uniform per wave)
+  const bool stages_k = D == 128 || tid < 128;
+  const int k_tok = D == 128 ? tid >> 4 : (tid & 127) >> 3, k_slice = tid & (kSlots - 1);
+  const int v_row = D == 128 ? tid >> 1 : (tid & 127) >> 1, v_half = tid & 1;
 
   // Physical block ids are read through the constant address space (scalar loads, the table
   // does not change during the launch) one chunk ahead of the K/V loads that need them, so
@@ -173,10 +180,13 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
   // alone it adds the loop-invariant 64-bit lane address to the block offset with a 64-bit vector
   // add per load, hence the two empty asm statements in fetch().
   const uint32_t k_piece = static_cast<uint32_t>(k_tok * D + k_slice * 8) * 2u;
-  const uint32_t v_piece = static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u;
+  const uint32_t v_piece = D == 128 || stages_v
+                               ? static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u
+                               : k_piece;
   const char* pool_h = reinterpret_cast<const char*>(a.pool + h * head_stride);
 
-  u32x4 stage_k[kChunkBlocks], stage_v[kChunkBlocks];
+  // d = 64: a thread stages K or V, not both; its pieces travel in stage_v, at offset v_piece
+  u32x4 stage_k[D == 128 ? kChunkBlocks : 1], stage_v[kChunkBlocks];
   // may_pass_end: the chunk can hold slots past the cache (only the item's last chunk can)
   auto fetch = [&](int c, auto may_pass_end) {   // uses the ids loaded by the preceding load_ids(c)
 #pragma unroll
@@ -192,9 +202,9 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
       asm("" : "+s"(base));
       asm("" : "+v"(kp), "+v"(vp));
       const gptr_t t = reinterpret_cast<gptr_t>(base);
-      stage_k[x] = *reinterpret_cast<gvec_t>(t + kp);
+      if constexpr (D == 128) stage_k[x] = *reinterpret_cast<gvec_t>(t + kp);
       u32x4 vv = *reinterpret_cast<gvec_t>(t + vp);
-      if (decltype(may_pass_end)::value &&
+      if (decltype(may_pass_end)::value && stages_v &&
           kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
         const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
         vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
@@ -209,10 +219,17 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
 #pragma unroll
     for (int x = 0; x < kChunkBlocks; ++x) {
       const int row = x * kBlockTokens + k_tok;
-      *reinterpret_cast<u32x4*>(&s_k[st][row * D + ((k_slice ^ k_tok) * 8)]) = stage_k[x];
+      uint16_t* krow = &s_k[st][row * D + ((k_slice ^ (D == 128 ? k_tok : (k_tok & (kSlots - 1)))) * 8)];
       uint16_t* vrow = &s_v[st][x * kTileElems + v_row * 8 + v_half * 4];
-      *reinterpret_cast<u32x2*>(vrow) = u32x2{stage_v[x].x, stage_v[x].y};                 // keys 8h+0..3 -> plane 0
-      *reinterpret_cast<u32x2*>(vrow + kVPlane) = u32x2{stage_v[x].z, stage_v[x].w};       // keys 8h+4..7 -> plane 1
+      if constexpr (D == 128) {
+        *reinterpret_cast<u32x4*>(krow) = stage_k[x];
+      } else if (stages_k) {
+        *reinterpret_cast<u32x4*>(krow) = stage_v[x];
+      }
+      if (stages_v) {
+        *reinterpret_cast<u32x2*>(vrow) = u32x2{stage_v[x].x, stage_v[x].y};                 // keys 8h+0..3 -> plane 0
+        *reinterpret_cast<u32x2*>(vrow + kVPlane) = u32x2{stage_v[x].z, stage_v[x].w};       // keys 8h+4..7 -> plane 1
+      }
     }
   };
 
@@ -249,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
       const int row = 32 * u + n;
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
-        const int slot = (2 * kk + hi) ^ (row & 15);
+        const int slot = (2 * kk + hi) ^ (row & (kSlots - 1));   // row & 15 at d = 128
         const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&s_k[st][row * D + slot * 8]));
         s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s[u], 0, 0, 0);
       }
@@ -362,14 +379,17 @@ __global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
 template <typename Launch>
 hipError_t launch_t(const Launch& a, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
-  hipLaunchKernelGGL((append_attn_kernel<128, Launch>), grid, dim3(256), 0, stream, a);
+  if (a.head_dim == 128)
+    hipLaunchKernelGGL((append_attn_kernel<128, Launch>), grid, dim3(256), 0, stream, a);
+  else
+    hipLaunchKernelGGL((append_attn_kernel<64, Launch>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
 bool append_shape_supported(int32_t group, int32_t head_dim) {
-  return head_dim == 128 && group >= 1 && group <= kMaxGroup;
+  return (head_dim == 128 || head_dim == 64) && group >= 1 && group <= kMaxGroup;
 }
 
 int32_t append_tile_rows(int32_t group) { return kTileRows / group; }

@@ -132,6 +132,9 @@ int32_t append_tile_rows(int32_t group);   // chunk rows per workgroup tile
 hipError_t launch_append_attn(const AppendLaunch& a, hipStream_t stream);
 // Same arguments for items whose tile has at most narrow_tile_rows(G) chunk rows (32 query rows
 // per kv head): the four waves split the keys instead of the rows, nothing is staged in LDS.
+inline bool narrow_shape_supported(int32_t group, int32_t head_dim) {   // what launch_narrow_attn accepts
+  return head_dim == 128 && group >= 1 && group <= 32;
+}
 int32_t narrow_tile_rows(int32_t group);
 hipError_t launch_narrow_attn(const AppendLaunch& a, hipStream_t stream);
 

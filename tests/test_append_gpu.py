@@ -30,11 +30,12 @@ RAGGED_L = [0, 1, 15, 16, 17, 100, 0, 500, 33, 1000]
 RAGGED_C = [1, 40, 1, 16, 33, 31, 130, 7, 64, 129]
 
 
-@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8), (6, 2), (10, 2), (40, 8), (12, 2), (14, 2),
-                                      (24, 1), (32, 1)])
-def test_ragged_append_all_head_shapes(n_q, n_kv):
-    c = small(40, RAGGED_L, RAGGED_C, n_q=n_q, n_kv=n_kv)
-    print("append ragged", n_q, n_kv, flush=True)
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 128), (2, 2, 128), (4, 2, 128), (16, 2, 128), (32, 8, 128), (6, 2, 128),
+                                        (10, 2, 128), (40, 8, 128), (12, 2, 128), (14, 2, 128), (24, 1, 128),
+                                        (32, 1, 128), (8, 2, 64), (2, 2, 64), (4, 2, 64), (16, 2, 64), (32, 8, 64)])
+def test_ragged_append_all_head_shapes(n_q, n_kv, d):
+    c = small(40, RAGGED_L, RAGGED_C, n_q=n_q, n_kv=n_kv, d=d)
+    print("append ragged", n_q, n_kv, d, flush=True)
     dc = DeviceCase(c)
     out, lse = dc.append()
     pool, ref, ref_lse, spread = oracle_append(c)
@@ -197,13 +198,14 @@ def test_single_long_trajectory_short_chunk_is_split_and_exact():
     assert_lse_close(lse, ref_lse, "split append lse")
 
 
-@pytest.mark.parametrize("n_q,n_kv", [(8, 2), (2, 2), (4, 2), (16, 2), (32, 8), (6, 2), (10, 2), (40, 8), (14, 2), (32, 1)])
-def test_short_multi_token_decode(n_q, n_kv):
+@pytest.mark.parametrize("n_q,n_kv,d", [(8, 2, 128), (2, 2, 128), (4, 2, 128), (16, 2, 128), (32, 8, 128), (6, 2, 128),
+                                        (10, 2, 128), (40, 8, 128), (14, 2, 128), (32, 1, 128), (8, 2, 64), (16, 2, 64)])
+def test_short_multi_token_decode(n_q, n_kv, d):
     """A verify step of speculative decoding: 2-8 new tokens on each of a few trajectories of very
     different lengths (ragged parts, L = 0 among them); default plan and one forced into many parts."""
     L = [0, 1, 63, 64, 65, 1000, 4097, 20000]
     C = [8, 2, 3, 5, 8, 4, 7, 6]
-    c = small(32, L, C, n_q, n_kv, 128)
+    c = small(32, L, C, n_q, n_kv, d)
     _, ref, ref_lse, spread = oracle_append(c)
     for kw in (dict(), dict(n_cu=1024, append_min_steps=1, max_split=64), dict(n_cu=16, max_split=3)):
         dc = DeviceCase(c, **kw)

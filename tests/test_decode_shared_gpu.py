@@ -65,11 +65,12 @@ def test_without_sharing_equals_plain_decode_bit_for_bit():
     assert np.array_equal(a_out, b_out) and np.array_equal(a_lse, b_lse)
 
 
-def test_head_dim_64_falls_back_to_private_reads():
+def test_groups_at_head_dim_64():
     group_of = [0, 0, 0, -1]
     c = shared_case(3, [400, 500, 330, 90], group_of, [20], n_q=8, n_kv=2, d=64)
     dc = DeviceCase(c)
-    assert dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])["n_groups"] == 0
+    plan = dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])
+    assert plan["n_groups"] == 1 and plan["group_prefix"][0] == 20
     out, lse = run_shared(dc)
     ref, ref_lse, spread = oracle_decode(c)
     assert_close(out, ref, "d64 shared", spread)

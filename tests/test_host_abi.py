@@ -230,7 +230,7 @@ def test_shared_plan_on_unsupported_head_dim_forms_no_groups():
     from tests.test_oracle_planner import csr
     tables = [[1, 2, 3, 4, 5, 6, 10], [1, 2, 3, 4, 5, 6, 11]]
     row_off, ids = csr(tables)
-    c = heddle.Context(8, 2, 64, 32)
+    c = heddle.Context(8, 2, 32, 32)          # host-only context; no kernel is built for head_dim 32
     plan = c.plan_decode_shared([100, 100], row_off, ids)
     assert plan["n_groups"] == 0 and plan["n_gitems"] == 0
     same_plan({**c.plan_decode([100, 100])}, {**plan, "n_items": plan["n_items"]})

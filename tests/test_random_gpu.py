@@ -81,7 +81,7 @@ def test_random_decode(seed):
 @pytest.mark.parametrize("seed", range(max(10, EXTRA)))
 def test_random_append(seed):
     rng = np.random.default_rng([102, seed])
-    shapes = [s for s in HEAD_SHAPES if s[2] == 128]
+    shapes = [s for s in HEAD_SHAPES if s[2] == 128 or s[0] // s[1] in POW2]
     n_q, n_kv, d = shapes[int(rng.integers(0, len(shapes)))]
     B = int(rng.integers(1, 13))
     L = draw_lengths(rng, B, int(rng.choice([200, 2000, 6000])))
@@ -110,7 +110,7 @@ def test_random_append(seed):
 def test_random_shared_decode(seed):
     rng = np.random.default_rng([103, seed])
     n_q, n_kv, d = [(8, 2, 128), (4, 1, 128), (16, 2, 128), (32, 8, 128), (2, 2, 128), (10, 2, 128), (40, 8, 128),
-                    (6, 2, 128)][int(rng.integers(0, 8))]
+                    (6, 2, 128), (8, 2, 64), (16, 4, 64)][int(rng.integers(0, 10))]
     n_groups = int(rng.integers(1, 5))
     group_of, lens, shared = [], [], []
     for g in range(n_groups):
