@@ -273,9 +273,11 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
  * The chunk's K/V rows are stored at positions L_b .. L_b+C_b-1 (the table must
  * already cover L_b + C_b tokens), then chunk row i attends to positions
  * 0 .. L_b+i: the whole retained context plus the chunk causally, itself
- * included.  L_b = 0 is legal (first prompt).
+ * included.  L_b = 0 is legal (first prompt).  With k and v both NULL the caller
+ * has stored the chunk's rows already (as with k_new / v_new of decode) and the
+ * call only attends.
  * Errors: B < 1, C_b < 1, L_b < 0, L_b + C_b > HEDDLE_MAX_CONTEXT, table too
- * short, NULL pointer -> INVAL. */
+ * short, a required pointer NULL, only one of k and v given -> INVAL. */
 typedef struct heddle_append_args {
   int32_t        B;
   const int32_t* ctx_len_host;   /* HOST   [B] L_b */
@@ -284,8 +286,8 @@ typedef struct heddle_append_args {
   const int32_t* row_off;        /* DEVICE [B+1] */
   const int32_t* block_ids;      /* DEVICE [row_off[B]] */
   const void*    q;              /* DEVICE bf16 [sum C][n_q][d] */
-  const void*    k;              /* DEVICE bf16 [sum C][n_kv][d] */
-  const void*    v;              /* DEVICE bf16 [sum C][n_kv][d] */
+  const void*    k;              /* DEVICE bf16 [sum C][n_kv][d] or NULL */
+  const void*    v;              /* DEVICE bf16 [sum C][n_kv][d] or NULL (both or neither) */
   void*          out;            /* DEVICE bf16 [sum C][n_q][d] */
   float*         lse;            /* DEVICE f32  [sum C][n_q] or NULL */
 } heddle_append_args;

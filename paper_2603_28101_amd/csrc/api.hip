@@ -841,8 +841,9 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
   const int32_t B = args->B;
   if (B < 1 || !args->ctx_len_host || !args->cu_chunk_host || !args->row_off_host || !args->row_off ||
-      !args->block_ids || !args->q || !args->k || !args->v || !args->out)
+      !args->block_ids || !args->q || !args->out)
     return HEDDLE_E_INVAL;
+  if ((args->k == nullptr) != (args->v == nullptr)) return HEDDLE_E_INVAL;
   if (args->cu_chunk_host[0] != 0 || args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
   for (int32_t b = 0; b < B; ++b) {
     const int64_t C = static_cast<int64_t>(args->cu_chunk_host[b + 1]) - args->cu_chunk_host[b];
@@ -949,7 +950,7 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
   ctx->enqueued = true;
   const int32_t* d = ctx->dev_plan;
 
-  {
+  if (args->k != nullptr) {
     KvWriteLaunch kw{};
     kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
     kw.row_off = args->row_off;

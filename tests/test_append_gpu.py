@@ -6,7 +6,7 @@ import pytest
 
 import heddle_workloads as hw
 from oracle import attention as oa
-from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64,
+from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, to_dev_bf16, bits_to_f64, torch_mod,
                             bf16_to_host_bits)
 
 pytestmark = pytest.mark.gpu
@@ -141,6 +141,29 @@ def test_append_needles():
         assert_lse_close(lse, ref_lse)
         for j in range(n_q):
             assert np.abs(out[:, j, (pos + j // G) % d] - 1000.0).max() < 8.0, (pos, j)
+
+
+def test_append_of_rows_the_caller_has_stored():
+    """k = v = NULL: the chunk's rows are in the pool already; the call attends and leaves the pool alone."""
+    torch = torch_mod()
+    c = small(47, [0, 10, 300, 31], [9, 1, 70, 33])
+    dc = DeviceCase(c)
+    out, lse = dc.append()                                   # stores the rows
+    pool_after = dc.pool_bits().copy()
+    out2 = torch.full(c["q"].shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse2 = torch.full(c["q"].shape[:2], float("nan"), dtype=torch.float32, device="cuda")
+    dc.ctx.attn_append(c["lens"], c["cu_chunk"], c["row_off"], dc.row_off, dc.block_ids, dc.q, None, None, out2, lse2)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_to_host_bits(out2), bf16_to_host_bits(dc.out))        # same kernels, same inputs
+    assert np.array_equal(lse2.cpu().numpy(), dc.lse.cpu().numpy())
+    assert np.array_equal(dc.pool_bits(), pool_after)
+    _, ref, ref_lse, spread = oracle_append(c)
+    assert_close(bits_to_f64(bf16_to_host_bits(out2)), ref, "append of stored rows", spread)
+    import paper_2603_28101_amd as heddle
+    with pytest.raises(heddle.HeddleError) as e:             # only one of the two
+        dc.ctx.attn_append(c["lens"], c["cu_chunk"], c["row_off"], dc.row_off, dc.block_ids, dc.q, dc.k_new, None,
+                           out2, lse2)
+    assert e.value.code == heddle.E_INVAL
 
 
 def test_append_rejects_bad_arguments():
