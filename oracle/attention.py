@@ -220,3 +220,11 @@ def unpack(pool_bits, dst_blocks, staged):
     """Inverse of pack under a (possibly different) list of physical blocks."""
     for i, blk in enumerate(dst_blocks):
         pool_bits[int(blk)] = staged[i]
+
+
+def copy_blocks(pool_bits, src_blocks, dst_blocks):
+    """Block dst[i] becomes a bit-for-bit copy of block src[i] (all kv heads, K and V, all 16 slots).
+    A sample that continues a shared prompt (16 samples per prompt, Sec. 7) names the prompt's whole
+    blocks in its own table and takes a copy of the partly filled last one, which it will write to."""
+    for s, d in zip(src_blocks, dst_blocks):
+        pool_bits[int(d)] = pool_bits[int(s)]

@@ -317,6 +317,30 @@ def test_pack_unpack_round_trip():
     assert np.array_equal(K1, K2) and np.array_equal(V1, V2)
 
 
+def test_copy_blocks_forks_a_trajectory():
+    """A fork: trajectory 1 names the whole blocks of trajectory 0 and a copy of its partly filled last
+    block.  Its gathered K/V (the gather is pinned by the flat-offset brute force) equals trajectory 0's,
+    the copy equals what pack and unpack would have moved, and no other block changes."""
+    c = small_case(37, [40, 7])
+    pool = c["pool"].copy()
+    row0 = [int(x) for x in c["block_ids"][: c["row_off"][1]]]            # 3 blocks, the last holds 8 tokens
+    free = [i for i in range(c["n_blocks"]) if i not in set(int(x) for x in c["block_ids"])]
+    assert free, "the generator over-provisions the pool"
+    fork_blk = free[0]
+    oa.copy_blocks(pool, [row0[2]], [fork_blk])
+    ids = np.concatenate([c["block_ids"], np.asarray(row0[:2] + [fork_blk], dtype=c["block_ids"].dtype)])
+    row_off = np.concatenate([c["row_off"], [len(ids)]]).astype(c["row_off"].dtype)
+    K0, V0 = oa.gather(pool, row_off, ids, 0, 40)
+    K2, V2 = oa.gather(pool, row_off, ids, 2, 40)
+    assert np.array_equal(K0, K2) and np.array_equal(V0, V2)
+    via_staging = c["pool"].copy()
+    oa.unpack(via_staging, [fork_blk], oa.pack(c["pool"], c["row_off"], c["block_ids"], 0, 40)[2:3])
+    assert np.array_equal(pool, via_staging)
+    untouched = [i for i in range(c["n_blocks"]) if i != fork_blk]
+    assert np.array_equal(pool[untouched], c["pool"][untouched])
+    assert not np.array_equal(pool[fork_blk], c["pool"][fork_blk])       # the free block held poison before
+
+
 def test_weight_spread_matches_direct_perturbation():
     """weight_spread is the first-order standard deviation of the output under independent
     relative perturbations of the weights; check it against an explicit finite perturbation."""
