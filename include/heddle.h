@@ -308,6 +308,17 @@ int heddle_kv_pack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, vo
 int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, const void* staging,
                      void* hip_stream);
 
+/* Copies whole blocks inside the pool, bit for bit: block dst[i] becomes a copy of
+ * block src[i].  For a sample that continues a shared prompt (16 samples per prompt,
+ * Sec. 7 "Workloads"): it names the prompt's whole blocks in its own table
+ * (heddle_kv_retain) and takes a copy of the partly filled last block, which it will
+ * write to.  Both lists are HOST arrays, read before the call returns; the copy is
+ * enqueued on the stream.
+ * Errors: an id outside [0, n_blocks), a destination named twice or also named as a
+ * source, n < 0 or a NULL list with n > 0 -> INVAL; no device -> UNSUPPORTED. */
+int heddle_kv_copy(heddle_ctx* ctx, int32_t n, const int32_t* src_block_ids_host, const int32_t* dst_block_ids_host,
+                   void* hip_stream);
+
 /* ---- trajectory placement (host only, no context) -----------------------------
  * Presorted dynamic programming of Sec. 5.2: n trajectories in DESCENDING length
  * order are split into at most m contiguous runs, one per worker, minimising

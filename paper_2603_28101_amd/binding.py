@@ -120,6 +120,7 @@ lib.heddle_attn_decode_shared.argtypes = [vp, C.POINTER(DecodeArgs), i32p, vp]
 lib.heddle_attn_append.argtypes = [vp, C.POINTER(AppendArgs), vp]
 lib.heddle_kv_pack.argtypes = [vp, C.c_int32, i32p, vp, vp]
 lib.heddle_kv_unpack.argtypes = [vp, C.c_int32, i32p, vp, vp]
+lib.heddle_kv_copy.argtypes = [vp, C.c_int32, i32p, i32p, vp]
 f64p = C.POINTER(C.c_double)
 lib.heddle_placement_dp.argtypes = [C.c_int32, f64p, i32p, C.c_int32, f64p, C.c_int32, C.c_double, C.c_int32,
                                     i32p, f64p]
@@ -136,7 +137,7 @@ lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_set_kv_pool", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_retain",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
-           "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_timing_enable",
+           "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_kv_copy", "heddle_timing_enable",
            "heddle_timing_read", "heddle_timing_samples", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
            "heddle_interference_table", "heddle_simulate_group",
            "heddle_version"):
@@ -422,6 +423,13 @@ class Context:
         need = a.shape[0] * self.n_kv_heads * 2 * 16 * self.head_dim
         _check(lib.heddle_kv_unpack(self._h, a.shape[0], p, _dptr(staging, "staging", 2, need), _stream_ptr(stream)),
                "heddle_kv_unpack")
+
+    def kv_copy(self, src_block_ids, dst_block_ids, stream=None) -> None:
+        s, sp = _i32(src_block_ids)
+        d, dp = _i32(dst_block_ids)
+        if s.shape[0] != d.shape[0]:
+            raise ValueError("kv_copy: as many destinations as sources")
+        _check(lib.heddle_kv_copy(self._h, s.shape[0], sp, dp, _stream_ptr(stream)), "heddle_kv_copy")
 
     # ---- measurement
     def timing_enable(self, every: int = 1) -> None:

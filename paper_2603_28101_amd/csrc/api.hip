@@ -1052,6 +1052,40 @@ int heddle_kv_unpack(heddle_ctx* ctx, int32_t n, const int32_t* block_ids_host, 
   return kv_move(ctx, false, n, block_ids_host, const_cast<void*>(staging), hip_stream);
 }
 
+int heddle_kv_copy(heddle_ctx* ctx, int32_t n, const int32_t* src_block_ids_host, const int32_t* dst_block_ids_host,
+                   void* hip_stream) {
+  if (ctx == nullptr || n < 0 || (n > 0 && (src_block_ids_host == nullptr || dst_block_ids_host == nullptr)))
+    return HEDDLE_E_INVAL;
+  const int64_t block_bytes =
+      static_cast<int64_t>(ctx->cfg.n_kv_heads) * 2 * HEDDLE_BLOCK_TOKENS * ctx->cfg.head_dim * 2;
+  for (int32_t i = 0; i < n; ++i)
+    if (src_block_ids_host[i] < 0 || src_block_ids_host[i] >= ctx->cfg.n_blocks || dst_block_ids_host[i] < 0 ||
+        dst_block_ids_host[i] >= ctx->cfg.n_blocks)
+      return HEDDLE_E_INVAL;
+  {   // every destination is written once and read by nobody in this call
+    std::vector<int32_t> dst(dst_block_ids_host, dst_block_ids_host + n);
+    std::sort(dst.begin(), dst.end());
+    if (std::adjacent_find(dst.begin(), dst.end()) != dst.end()) return HEDDLE_E_INVAL;
+    for (int32_t i = 0; i < n; ++i)
+      if (std::binary_search(dst.begin(), dst.end(), src_block_ids_host[i])) return HEDDLE_E_INVAL;
+  }
+  if (!ctx->has_device || block_bytes % 4096 != 0) return HEDDLE_E_UNSUPPORTED;
+  if (n == 0) return HEDDLE_OK;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  StagingSlot* slot = nullptr;
+  int rc = acquire_slot(ctx, 2 * static_cast<size_t>(n), &slot);
+  if (rc != HEDDLE_OK) return rc;
+  std::memcpy(slot->host, src_block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
+  std::memcpy(slot->host + n, dst_block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
+  rc = upload(ctx, slot, 2 * static_cast<size_t>(n), stream);
+  if (rc != HEDDLE_OK) return rc;
+  ctx->enqueued = true;
+  HEDDLE_HIP(launch_kv_copy(ctx->cfg.kv_pool, ctx->dev_plan, n, block_bytes, stream));
+  return HEDDLE_OK;
+}
+
 int heddle_timing_enable(heddle_ctx* ctx, int32_t on) {
   if (ctx == nullptr) return HEDDLE_E_INVAL;
   if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;

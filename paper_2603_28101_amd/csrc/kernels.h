@@ -143,6 +143,10 @@ hipError_t launch_narrow_attn(const AppendLaunch& a, hipStream_t stream);
 hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* ids, int32_t n, int64_t block_bytes,
                           hipStream_t stream);
 
+// Copies n whole blocks inside the pool: block ids[n + i] becomes a copy of block ids[i] (ids is a
+// device array of 2n entries; no destination may also be a source or appear twice).
+hipError_t launch_kv_copy(void* pool, const int32_t* ids, int32_t n, int64_t block_bytes, hipStream_t stream);
+
 hipError_t launch_stream_read(const void* src, uint64_t bytes, uint32_t* sink, hipStream_t stream);
 
 // Copies n_vec 16-byte pieces from pinned host memory (src, device-visible) to device memory in a

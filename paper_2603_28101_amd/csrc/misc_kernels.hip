@@ -101,6 +101,18 @@ __global__ __launch_bounds__(256) void kv_move_kernel(uint16_t* pool, uint16_t* 
     __builtin_nontemporal_store(__builtin_nontemporal_load(s), p);
 }
 
+// Block ids[n + i] of the pool becomes a copy of block ids[i]; same slicing as kv_move_kernel.
+__global__ __launch_bounds__(256) void kv_copy_kernel(uint16_t* pool, const int32_t* ids, int32_t n,
+                                                       int32_t slices_per_block) {
+  const int i = blockIdx.x / slices_per_block;
+  const int slice = blockIdx.x - i * slices_per_block;
+  const int64_t block_elems = static_cast<int64_t>(slices_per_block) * 2048;
+  const int64_t off = slice * 2048 + threadIdx.x * 8;
+  const u32x4* s = reinterpret_cast<const u32x4*>(pool + static_cast<int64_t>(ids[i]) * block_elems + off);
+  u32x4* d = reinterpret_cast<u32x4*>(pool + static_cast<int64_t>(ids[n + i]) * block_elems + off);
+  __builtin_nontemporal_store(__builtin_nontemporal_load(s), d);
+}
+
 // The plan image of a call goes from the pinned staging buffer to device memory in this kernel
 // rather than in a hipMemcpyAsync: between two kernels of a stream the runtime's copy of more than
 // 16 KB costs about 17 us (it leaves the compute queue), this kernel 3-4 us for 20-64 KB.
@@ -174,6 +186,14 @@ hipError_t launch_kv_move(bool pack, void* pool, void* staging, const int32_t* i
   else
     hipLaunchKernelGGL(kv_move_kernel<false>, grid, dim3(256), 0, stream, static_cast<uint16_t*>(pool),
                        static_cast<uint16_t*>(staging), ids, slices);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_copy(void* pool, const int32_t* ids, int32_t n, int64_t block_bytes, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int32_t slices = static_cast<int32_t>(block_bytes / 4096);
+  const dim3 grid(static_cast<unsigned>(n) * static_cast<unsigned>(slices));
+  hipLaunchKernelGGL(kv_copy_kernel, grid, dim3(256), 0, stream, static_cast<uint16_t*>(pool), ids, n, slices);
   return hipGetLastError();
 }
 

@@ -108,6 +108,36 @@ def test_empty_and_errors():
         dc.ctx.kv_unpack(np.array([1, 1], dtype=np.int32), st)
 
 
+@pytest.mark.parametrize("n_kv,d", [(2, 128), (8, 128), (2, 64), (1, 128)])
+def test_copy_blocks_matches_oracle(n_kv, d):
+    """heddle_kv_copy: forks of blocks inside the pool, bit for bit, nothing else touched; then a
+    trajectory that names the copies decodes like the one that names the originals."""
+    import paper_2603_28101_amd as heddle
+    torch = torch_mod()
+    case = _case(seed=5, lens=(700, 1, 16, 17, 33), n_q=n_kv * 4, n_kv=n_kv, d=d)
+    dc = DeviceCase(case)
+    used = set(int(x) for x in case["block_ids"])
+    free = [i for i in range(case["n_blocks"]) if i not in used]
+    row0 = case["block_ids"][case["row_off"][0]:case["row_off"][1]]
+    n = min(len(free), len(row0))
+    assert n >= 5
+    src, dst = np.asarray(row0[:n], dtype=np.int32), np.asarray(free[:n], dtype=np.int32)
+    pool = case["pool"].copy()
+    oa.copy_blocks(pool, src, dst)
+    dc.ctx.kv_copy(src, dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(dc.pool_bits(), pool)
+    dc.ctx.kv_copy(np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.int32))      # nothing to do
+    for bad_src, bad_dst in (([int(src[0])], [case["n_blocks"]]), ([-1], [int(dst[0])]),
+                             ([int(src[0]), int(src[1])], [int(dst[0]), int(dst[0])]),     # a destination twice
+                             ([int(src[0]), int(dst[1])], [int(dst[1]), int(dst[2])])):    # a destination is a source
+        with pytest.raises(heddle.HeddleError) as e:
+            dc.ctx.kv_copy(np.asarray(bad_src, dtype=np.int32), np.asarray(bad_dst, dtype=np.int32))
+        assert e.value.code == heddle.E_INVAL
+    torch.cuda.synchronize()
+    assert np.array_equal(dc.pool_bits(), pool)
+
+
 def test_pack_of_the_benchmark_workload_at_full_size():
     """The launch `bench.py --op pack` times: every block of the Qwen3-8B decode workload (1.77 GB)
     gathered in one call; all bytes compared, then scattered back into a cleared pool."""

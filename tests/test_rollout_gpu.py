@@ -123,18 +123,24 @@ def test_rollout_of_six_trajectories():
 
     # 1. prefill the two prompts once each (trajectories 0 and 3)
     w.append([0, 3], prompts, "prompt prefill")
-    # the other samples of a prompt start from its whole blocks (shared physically) and copy the
-    # partly filled last block into a block of their own
+    # the other samples of a prompt start from its whole blocks (shared physically: one more holder
+    # each) and from a copy of its partly filled last block (8 and 11 tokens) in a block of their own
     for leader, members in ((0, (1, 2)), (3, (4, 5))):
         whole = w.lens[leader] // 16
+        assert w.lens[leader] % 16 != 0
         for b in members:
             w.tables[b] = list(w.tables[leader][:whole])
-            w.lens[b] = whole * 16
-            w.ctx.kv_retain(np.asarray(w.tables[b], dtype=np.int32))      # one more holder of the prompt's blocks
+            w.ctx.kv_retain(np.asarray(w.tables[b], dtype=np.int32))
             assert w.ref_blocks.retain(w.tables[b]) == 0
-    tail = [w.lens[0] - (w.lens[0] // 16) * 16, w.lens[3] - (w.lens[3] // 16) * 16]     # 8 and 11 tokens
-    # re-append those tail tokens for the members (in a real rollout: a copy; here fresh rows)
-    w.append([1, 2, 4, 5], [tail[0], tail[0], tail[1], tail[1]], "prompt tails of the other samples")
+            w.lens[b] = whole * 16
+            w.grow(b, w.lens[leader])                                     # the block for the copy
+            w.lens[b] = w.lens[leader]
+        src = [w.tables[leader][whole]] * len(members)
+        dst = [w.tables[b][whole] for b in members]
+        w.ctx.kv_copy(np.asarray(src, dtype=np.int32), np.asarray(dst, dtype=np.int32))
+        oa.copy_blocks(w.ref_pool, src, dst)
+    torch.cuda.synchronize()
+    w.check_pool("forks of the prompts' last blocks")
     assert w.lens == [200, 200, 200, 75, 75, 75]
 
     # 2. a few decode steps for everybody, shared-prefix path (12 and 4 whole prompt blocks)
