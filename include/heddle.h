@@ -27,6 +27,8 @@
  *              [head_dim][16] (the 16 tokens of one head-dim element are contiguous)
  *   block table in CSR form: token position p of trajectory b is stored in
  *              block  block_ids[row_off[b] + p / 16], slot p % 16
+ *              (a row may be longer than its trajectory needs; entries behind the
+ *              needed blocks are never read as addresses)
  *   q / out    bf16 [rows][n_q_heads][head_dim]
  *   k / v rows bf16 [rows][n_kv_heads][head_dim]
  * Slots past a trajectory's length and blocks outside every table may hold

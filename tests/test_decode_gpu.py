@@ -412,3 +412,57 @@ def test_one_context_serves_a_pool_per_layer():
         assert np.array_equal(bf16_to_host_bits(dev_pools[layer]), host_pools[layer]), f"pool of layer {layer}"
     with pytest.raises(Exception):
         dc.ctx.set_kv_pool(torch.empty(16, dtype=torch.bfloat16, device="cuda"))       # too small for the context
+
+
+def test_table_entries_past_the_needed_blocks_are_never_read():
+    """A table row may be longer than its trajectory needs (blocks reserved ahead, or stale entries):
+    what stands behind the needed blocks, here -1, INT32_MAX and an id just past the pool, is never
+    used as an address.  Decode, shared-prefix decode and append give the bits of the exact table."""
+    torch = torch_mod()
+    group_of = [0, 0, 0, -1, -1]
+    lens = np.array([330, 500, 421, 17, 2100], dtype=np.int32)
+    c = hw.build_case(entropy=[0, 61], lens=lens, n_q_heads=8, n_kv_heads=2, head_dim=128, threads=4,
+                      group_of=np.asarray(group_of), shared_blocks=np.asarray([20]))
+    junk = [-1, 2 ** 31 - 1, c["n_blocks"], -(2 ** 31)]
+    rows = [list(c["block_ids"][c["row_off"][b]:c["row_off"][b + 1]]) for b in range(5)]
+    need = [-(-int(n) // 16) for n in lens]
+    padded = [r[:n] + junk[: 1 + b % 4] for b, (r, n) in enumerate(zip(rows, need))]
+    p_off = np.concatenate([[0], np.cumsum([len(r) for r in padded])]).astype(np.int32)
+    p_ids = np.asarray([x for r in padded for x in r], dtype=np.int64).astype(np.int32)
+    exact = DeviceCase(c)
+    dirty = DeviceCase(dict(c, row_off=p_off, block_ids=p_ids))
+    rng = np.random.default_rng(4)
+    k_new = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((5, 2, 128), dtype=np.float32)))
+    v_new = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((5, 2, 128), dtype=np.float32)))
+    for dc in (exact, dirty):
+        dc.decode(k_new=k_new, v_new=v_new)
+    assert np.array_equal(bf16_to_host_bits(dirty.out), bf16_to_host_bits(exact.out))
+    assert np.array_equal(dirty.lse.cpu().numpy(), exact.lse.cpu().numpy())
+    for dc in (exact, dirty):
+        cc = dc.case
+        assert dc.ctx.plan_decode_shared(cc["lens"], cc["row_off"], cc["block_ids"])["n_groups"] == 1
+        dc.out.fill_(float("nan"))
+        dc.ctx.attn_decode_shared(cc["lens"], cc["row_off"], cc["block_ids"], dc.row_off, dc.block_ids, dc.q, dc.out,
+                                  dc.lse)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_to_host_bits(dirty.out), bf16_to_host_bits(exact.out))
+    assert np.array_equal(dirty.pool_bits(), exact.pool_bits())
+    ref, ref_lse, spread = oa.decode(exact.pool_bits(), c["row_off"], c["block_ids"], lens, c["q"], 2, with_spread=True,
+                                     centered=None)
+    assert_close(bits_to_f64(bf16_to_host_bits(dirty.out)), ref, "shared decode over a padded table", spread)
+    # append of 3 tokens onto contexts shortened by 3: the rows written and attended lie inside the needed blocks
+    chunk = np.full(5, 3, dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(chunk)]).astype(np.int32)
+    q3 = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((15, 8, 128), dtype=np.float32)))
+    k3 = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((15, 2, 128), dtype=np.float32)))
+    v3 = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((15, 2, 128), dtype=np.float32)))
+    outs = []
+    for dc in (exact, dirty):
+        cc = dc.case
+        o = torch.full((15, 8, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dc.ctx.attn_append(lens - 3, cu, cc["row_off"], dc.row_off, dc.block_ids, q3, k3, v3, o, None)
+        outs.append(o)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_to_host_bits(outs[1]), bf16_to_host_bits(outs[0]))
+    assert np.isfinite(bits_to_f64(bf16_to_host_bits(outs[1]))).all()
+    assert np.array_equal(dirty.pool_bits(), exact.pool_bits())
