@@ -217,6 +217,26 @@ typedef struct heddle_decode_args {
 } heddle_decode_args;
 int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream);
 
+/* ---- decode without allocation ----------------------------------------------
+ * For callers that cannot allocate device memory while they run: code inside a HIP
+ * graph capture, a serving loop that must not stall on the allocator, a harness that
+ * forbids hipMalloc.  Same arguments, result and errors as heddle_attn_decode, same
+ * kernels; the plan image and the split-K partials live in a static device array of
+ * the library (64 KiB + 16 MiB, one copy per GPU that loads the library, held until
+ * the process ends) instead of the context's grow-only scratch.  The call makes no
+ * hipMalloc, hipFree, hipHostMalloc or other allocating HIP call and does not
+ * synchronise for memory; the pinned staging ring it copies the plan from was sized
+ * for it when the context was created.
+ * Limits: plan image 8*n_items + 4*B + 1 <= 16384 words and partials
+ * n_items * n_q_heads * (head_dim + 4) * 4 bytes <= 16 MiB (n_items as returned by
+ * heddle_plan_decode; 992 items at 32 query heads of 128).  A larger call returns
+ * HEDDLE_E_NOMEM before anything is enqueued, heddle_last_error_detail() says which
+ * limit.  Nothing in the array has to start at zero (every partial that is read was
+ * written by the same call).  All contexts of a GPU share its array: two such calls
+ * that overlap in time on one GPU (different streams, or different contexts) race
+ * and give wrong results; calls on one stream are ordered and safe. */
+int heddle_attn_decode_static(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream);
+
 /* ---- decode with shared prefixes --------------------------------------------
  * The samples of one prompt (16 per prompt in the paper's rollouts, Sec. 7
  * "Workloads") start with the same tokens, and a prefix-cache hit (Sec. 2.3,
@@ -384,7 +404,8 @@ int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us
 int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream);
 
 const char* heddle_strerror(int code);
-/* Text of the HIP call that made the calling thread's last HEDDLE_E_HIP (empty if none). */
+/* Text of the HIP call that made the calling thread's last HEDDLE_E_HIP, or of the limit that its
+ * last heddle_attn_decode_static call exceeded (empty if neither happened yet). */
 const char* heddle_last_error_detail(void);
 int heddle_version(void);
 

@@ -114,6 +114,7 @@ lib.heddle_kv_num_free.argtypes = [vp, i32p]
 lib.heddle_plan_decode.argtypes = [vp, C.c_int32, i32p, C.POINTER(Plan)]
 lib.heddle_plan_append.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendPlan)]
 lib.heddle_attn_decode.argtypes = [vp, C.POINTER(DecodeArgs), vp]
+lib.heddle_attn_decode_static.argtypes = [vp, C.POINTER(DecodeArgs), vp]
 lib.heddle_plan_append_split.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(AppendSplitPlan)]
 lib.heddle_plan_decode_shared.argtypes = [vp, C.c_int32, i32p, i32p, i32p, C.POINTER(SharedPlan)]
 lib.heddle_attn_decode_shared.argtypes = [vp, C.POINTER(DecodeArgs), i32p, vp]
@@ -137,6 +138,7 @@ lib.heddle_last_error_detail.restype = C.c_char_p
 for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_set_kv_pool", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_retain",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
+           "heddle_attn_decode_static",
            "heddle_attn_append", "heddle_plan_decode_shared", "heddle_attn_decode_shared", "heddle_plan_append_split", "heddle_kv_pack", "heddle_kv_unpack", "heddle_kv_copy", "heddle_timing_enable",
            "heddle_timing_read", "heddle_timing_samples", "heddle_stream_read", "heddle_placement_dp", "heddle_placement_aggregate",
            "heddle_interference_table", "heddle_simulate_group",
@@ -147,7 +149,9 @@ for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_set_kv_pool", 
 class HeddleError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        detail = lib.heddle_last_error_detail().decode() if code == E_HIP else ""
+        # the detail text belongs to a failed HIP call, or names the limit a static-scratch call exceeded
+        detail = (lib.heddle_last_error_detail().decode()
+                  if code == E_HIP or (code == E_NOMEM and where.endswith("_static")) else "")
         super().__init__(f"{where}: {lib.heddle_strerror(code).decode()} ({code}) {detail}")
 
 
@@ -373,6 +377,15 @@ class Context:
         ro_a, ro_p = _i32(row_off_host)
         args = self._decode_args(lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new)
         _check(lib.heddle_attn_decode(self._h, C.byref(args), _stream_ptr(stream)), "heddle_attn_decode")
+
+    def attn_decode_static(self, lens, row_off_host, row_off, block_ids, q, out, lse=None, k_new=None,
+                           v_new=None, stream=None) -> None:
+        """heddle_attn_decode with the library's static device scratch: allocates nothing."""
+        lens_a, lens_p = _i32(lens)
+        ro_a, ro_p = _i32(row_off_host)
+        args = self._decode_args(lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new)
+        _check(lib.heddle_attn_decode_static(self._h, C.byref(args), _stream_ptr(stream)),
+               "heddle_attn_decode_static")
 
     def _decode_args(self, lens_a, lens_p, ro_a, ro_p, row_off, block_ids, q, out, lse, k_new, v_new):
         B = lens_a.shape[0]

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -23,6 +24,14 @@ constexpr int kGuards = kStagingSlots / kUploadsPerGuard;
 constexpr int kTimedKernels = 8;       // split-K decode, combine, append, kv write, pack, unpack, shared prefix,
                                        // narrow append
 constexpr int kEventPairs = 2048;      // per timed kernel; older records are overwritten
+
+// Scratch of heddle_attn_decode_static: device memory that is part of the library's code object
+// instead of the heap.  Layout: plan image [kStaticPlanWords] | partial sums | partial (max, sum)
+// records, each region starting at a multiple of 256 bytes.
+constexpr size_t kStaticPlanWords = 16384;                       // 64 KiB
+constexpr size_t kStaticPartBytes = size_t{16} << 20;            // 16 MiB for both partial arrays
+constexpr size_t kStaticBytes = kStaticPlanWords * sizeof(int32_t) + kStaticPartBytes + 256;
+constexpr int kMaxDevices = 64;
 
 struct StagingSlot {
   int32_t* host = nullptr;             // pinned
@@ -47,6 +56,10 @@ struct KernelTimer {
 
 }  // namespace
 
+// One copy per GPU that loads the library, held until the process ends.  Host code never uses this
+// name as an address: static_scratch_of() asks the runtime where the current device keeps it.
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
 struct heddle_ctx {
   heddle_config cfg{};
   PlanParams plan{};
@@ -66,6 +79,7 @@ struct heddle_ctx {
   size_t dev_part_acc_elems = 0;
   float* dev_part_ml = nullptr;
   size_t dev_part_ml_elems = 0;
+  unsigned char* static_scratch = nullptr;   // this device's copy of `scratch` (nullptr: lookup failed)
 
   int32_t timing_every = 0;             // 0 = off; N = record every N-th launch of each kernel
   KernelTimer timers[kTimedKernels];
@@ -130,7 +144,8 @@ int grow_device(void** ptr, size_t* have, size_t want, size_t elem_bytes) {
 // Takes the next pinned staging slot, waiting for the copy that last read it: for the oldest
 // guard recorded at or after that upload (with 8 slots and a guard every 4th upload there is
 // one unless calls failed in between; then the device is synchronised).
-int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
+int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out, bool may_allocate = true) {
+  if (!may_allocate && words > ctx->staging[ctx->next_slot].cap_words) return HEDDLE_E_NOMEM;
   StagingSlot& s = ctx->staging[ctx->next_slot];
   ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
   if (s.used_at != 0) {
@@ -165,11 +180,10 @@ int acquire_slot(heddle_ctx* ctx, size_t words, StagingSlot** out) {
 // The image is copied by a kernel that reads the pinned buffer (see plan_copy_kernel), in whole
 // 16-byte pieces: both buffers are sized in multiples of four words.
 // With `rows` the same launch stores the new K/V row of every trajectory of a decode step.
-int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream, const KvWriteLaunch* rows = nullptr) {
+int upload_to(heddle_ctx* ctx, StagingSlot* s, size_t words, int32_t* dst, hipStream_t stream,
+              const KvWriteLaunch* rows = nullptr) {
   const size_t padded = (words + 3) & ~static_cast<size_t>(3);
-  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
-  if (rc != HEDDLE_OK) return rc;
-  HEDDLE_HIP(launch_plan_copy(s->host_dev, ctx->dev_plan, padded / 4, rows, stream));
+  HEDDLE_HIP(launch_plan_copy(s->host_dev, dst, padded / 4, rows, stream));
   s->used_at = ++ctx->uploads;
   if (ctx->uploads % kUploadsPerGuard == 0) {
     UploadGuard& g = ctx->guards[ctx->next_guard];
@@ -179,6 +193,35 @@ int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream, co
     g.pending = true;
   }
   return HEDDLE_OK;
+}
+
+// Upload into the context's own plan buffer, grown first if the image does not fit.
+int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream, const KvWriteLaunch* rows = nullptr) {
+  const size_t padded = (words + 3) & ~static_cast<size_t>(3);
+  const int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
+  if (rc != HEDDLE_OK) return rc;
+  return upload_to(ctx, s, words, ctx->dev_plan, stream, rows);
+}
+
+// Address of `scratch` on the current device, asked once per device and kept.
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kMaxDevices] = {};
+bool g_static_asked[kMaxDevices] = {};
+
+unsigned char* static_scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_asked[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) {
+      (void)hip_failed(e, "hipGetSymbolAddress(scratch)", __LINE__);
+      p = nullptr;
+    }
+    g_static_ptr[device] = static_cast<unsigned char*>(p);
+    g_static_asked[device] = true;
+  }
+  return g_static_ptr[device];
 }
 
 struct TimedScope {
@@ -272,6 +315,25 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
         return hip_failed(e, "hipEventCreateWithFlags", __LINE__);
       }
     }
+    // every staging slot starts large enough for the biggest plan image the static-scratch entry
+    // point accepts, which then never meets a slot it would have to enlarge
+    for (StagingSlot& sl : ctx->staging) {
+      void* p = nullptr;
+      hipError_t e = hipHostMalloc(&p, kStaticPlanWords * sizeof(int32_t), hipHostMallocDefault);
+      if (e == hipSuccess) {
+        sl.host = static_cast<int32_t*>(p);
+        sl.cap_words = kStaticPlanWords;
+        e = hipHostGetDevicePointer(&sl.host_dev, p, 0);
+      }
+      if (e != hipSuccess) {
+        release_device_objects(ctx.get());
+        return hip_failed(e, "hipHostMalloc (staging ring)", __LINE__);
+      }
+    }
+    ctx->static_scratch = static_scratch_of(cfg->device);
+    ctx->items.reserve(kStaticPlanWords / 8);
+    ctx->nsplit.reserve(kStaticPlanWords / 4);
+    ctx->part_off.reserve(kStaticPlanWords / 4 + 1);
     ctx->has_device = true;
   } else if (n_cu == 0) {
     n_cu = 256;
@@ -692,7 +754,11 @@ int heddle_plan_append_split(const heddle_ctx* ctx, int32_t B, const int32_t* ct
   return HEDDLE_OK;
 }
 
-int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+namespace {
+
+// The decode step behind heddle_attn_decode (scratch on the heap, grown when a call needs more) and
+// heddle_attn_decode_static (scratch in the library's static device array, nothing allocated).
+int decode_step(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream, bool static_scratch) {
   {
     const int rc_args = check_decode_args(ctx, args);
     if (rc_args != HEDDLE_OK) return rc_args;
@@ -709,23 +775,6 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   const size_t n_parts = static_cast<size_t>(ctx->part_off[B]);
   const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
 
-  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems,
-                       n_parts * Hq * D, sizeof(float));
-  if (rc != HEDDLE_OK) return rc;
-  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 4,
-                   sizeof(float));
-  if (rc != HEDDLE_OK) return rc;
-
-  // plan image: item records | trajectory records | first_pos[B] | cu_rows[B+1]
-  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 2 * static_cast<size_t>(B) + 1;
-  StagingSlot* slot = nullptr;
-  rc = acquire_slot(ctx, words, &slot);
-  if (rc != HEDDLE_OK) return rc;
-  int32_t* w = slot->host;
-  DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
-  DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * n_items);
-  int32_t* h_first = w + 8 * n_items + 2 * static_cast<size_t>(B);
-  int32_t* h_cu = h_first + B;
   // With 8 query heads per kv head the packed-dot kernel is bound by its arithmetic; the
   // matrix-core kernel for short-row tiles, fed the same plan as an append of one token per
   // trajectory, is not.  It cuts keys at multiples of 64, so every item must start there.
@@ -736,6 +785,48 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   for (size_t i = 0; i < n_items && on_matrix_cores; ++i)
     on_matrix_cores = ctx->items[i].blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
   if (!on_matrix_cores && !splitk_built) return HEDDLE_E_UNSUPPORTED;
+
+  // plan image: item records | trajectory records | first_pos[B] | cu_rows[B+1]
+  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 2 * static_cast<size_t>(B) + 1;
+  const size_t acc_elems = n_parts * Hq * D, ml_elems = n_parts * Hq * 4;
+  int32_t* dev_plan = nullptr;
+  float *part_acc = nullptr, *part_ml = nullptr;
+  int rc = HEDDLE_OK;
+  if (static_scratch) {
+    if (ctx->static_scratch == nullptr) {
+      std::snprintf(g_detail, sizeof(g_detail), "hipGetSymbolAddress(scratch) failed when the context was created");
+      return HEDDLE_E_HIP;
+    }
+    const size_t acc_bytes = (acc_elems * sizeof(float) + 255) & ~size_t{255};
+    if (((words + 3) & ~size_t{3}) > kStaticPlanWords || acc_bytes + ml_elems * sizeof(float) > kStaticPartBytes) {
+      std::snprintf(g_detail, sizeof(g_detail),
+                    "static scratch too small: plan image %zu words (limit %zu), partials %zu bytes (limit %zu)",
+                    words, kStaticPlanWords, acc_bytes + ml_elems * sizeof(float), kStaticPartBytes);
+      return HEDDLE_E_NOMEM;
+    }
+    dev_plan = reinterpret_cast<int32_t*>(ctx->static_scratch);
+    part_acc = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t));
+    part_ml = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t) + acc_bytes);
+  } else {
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, acc_elems, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, ml_elems, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, (words + 3) & ~size_t{3},
+                     sizeof(int32_t));
+    if (rc != HEDDLE_OK) return rc;
+    dev_plan = ctx->dev_plan;
+    part_acc = ctx->dev_part_acc;
+    part_ml = ctx->dev_part_ml;
+  }
+  StagingSlot* slot = nullptr;
+  rc = acquire_slot(ctx, words, &slot, !static_scratch);
+  if (rc != HEDDLE_OK) return rc;
+  int32_t* w = slot->host;
+  DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
+  DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * n_items);
+  int32_t* h_first = w + 8 * n_items + 2 * static_cast<size_t>(B);
+  int32_t* h_cu = h_first + B;
   for (size_t i = 0; i < n_items; ++i) {
     const DecodeItem& it = ctx->items[i];
     if (on_matrix_cores) {
@@ -784,9 +875,9 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     kw.head_dim = D;
     kw.one_row_each = 1;
   }
-  rc = upload(ctx, slot, words, stream, args->k_new != nullptr ? &kw : nullptr);
+  rc = upload_to(ctx, slot, words, dev_plan, stream, args->k_new != nullptr ? &kw : nullptr);
   if (rc != HEDDLE_OK) return rc;
-  const int32_t* d = ctx->dev_plan;
+  const int32_t* d = dev_plan;
   ctx->enqueued = true;
 
   DecodeLaunch dl{};
@@ -795,8 +886,8 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
   dl.items = reinterpret_cast<const DecodeItemRec*>(d);
   dl.trajs = reinterpret_cast<const DecodeTrajRec*>(d + 8 * n_items);
   dl.q = static_cast<const uint16_t*>(args->q);
-  dl.part_acc = ctx->dev_part_acc;
-  dl.part_ml = ctx->dev_part_ml;
+  dl.part_acc = part_acc;
+  dl.part_ml = part_ml;
   dl.out = static_cast<uint16_t*>(args->out);
   dl.lse = args->lse;
   dl.B = B;
@@ -834,6 +925,16 @@ int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hi
     HEDDLE_HIP(launch_decode_combine(dl, stream));
   }
   return HEDDLE_OK;
+}
+
+}  // namespace
+
+int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+  return decode_step(ctx, args, hip_stream, false);
+}
+
+int heddle_attn_decode_static(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
+  return decode_step(ctx, args, hip_stream, true);
 }
 
 int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream) {

@@ -41,10 +41,13 @@ void plan_decode(const PlanParams& p, int32_t B, const int32_t* len, std::vector
       items.push_back(it);
     }
   }
-  // longest first; (b, s) ascending among equals.  Items were generated in (b, s)
-  // order, so a stable sort on size alone gives exactly that order.
-  std::stable_sort(items.begin(), items.end(), [](const DecodeItem& x, const DecodeItem& y) {
-    return (x.blk_end - x.blk_begin) > (y.blk_end - y.blk_begin);
+  // longest first; (b, s) ascending among equals.  The key is total, so an in-place sort gives
+  // one order and the call takes no work buffer from the heap.
+  std::sort(items.begin(), items.end(), [](const DecodeItem& x, const DecodeItem& y) {
+    const int32_t nx = x.blk_end - x.blk_begin, ny = y.blk_end - y.blk_begin;
+    if (nx != ny) return nx > ny;
+    if (x.b != y.b) return x.b < y.b;
+    return x.s < y.s;
   });
 }
 
