@@ -26,12 +26,19 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector rate (packed); two-way bf16 dot instructions run at the same rate
+FP32_FMA_PEAK_TFLOPS = 78.6       # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz: plain (unpacked) fp32 FMA
+PER_CONFIG = (3, 4, 5)            # the other named full-size workloads, reported after the headline
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8, 9])
+    ap.add_argument("--workload", type=int, default=None, choices=[2, 3, 4, 5, 6, 7, 8, 9],
+                    help="one workload only; default: workload 2 as the headline plus per_config entries for "
+                         "workloads 3, 4 and 5")
     ap.add_argument("--op", default="attention", choices=["attention", "pack", "placement"],
                     help="attention: the workload's decode or append pass (default); pack: gather of every "
                          "trajectory's blocks into one contiguous staging buffer (whole-block copy); placement: decode step time per batch size -> interference table -> "
@@ -55,11 +62,33 @@ def main():
     import paper_2603_28101_amd as heddle
 
     torch.cuda.set_device(0)
+    mods = (np, torch, hw, heddle)
     if args.op == "placement":
         print(json.dumps(run_placement(args, np, torch, hw, heddle)))
         return
-    w = hw.WORKLOADS[args.workload]
-    case = hw.make_workload(args.workload, args.seed, threads=min(16, os.cpu_count() or 1))
+    if args.workload is not None or args.op == "pack":
+        print(json.dumps(measure(args, args.workload or 2, mods, cpu_budget_s=20.0)))
+        return
+    result = measure(args, 2, mods, cpu_budget_s=15.0)
+    per_config = {}
+    for cfg in PER_CONFIG:
+        r = measure(args, cfg, mods, cpu_budget_s=8.0)
+        per_config[r["config"]["workload"]] = {
+            k: r[k] for k in ("metric", "value", "unit", "ms_per_step", "us_per_step", "step_us_p10_p50_p90",
+                              "frac_of_hbm_peak_whole_step", "frac_of_mfma_peak_whole_step", "roofline",
+                              "alu_ceiling", "cpu_baseline", "config") if k in r}
+    result["per_config"] = per_config
+    print(json.dumps(result))
+
+
+def measure(args, workload, mods, cpu_budget_s):
+    """Times one workload; returns the result record.  Three passes over the same resident inputs:
+    (1) wall clock of `steps` whole steps with the library's timers off: `value`; (2) the same
+    steps with one event per step boundary: spread of the whole step; (3) the same steps with an
+    event pair around every kernel launch: the roofline of the dominant kernel."""
+    np, torch, hw, heddle = mods
+    w = hw.WORKLOADS[workload]
+    case = hw.make_workload(workload, args.seed, threads=min(16, os.cpu_count() or 1))
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
@@ -133,19 +162,30 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events around every 8th launch of each kernel (every launch of a short run), on the
-    # launch stream: an event record costs several microseconds of stream time, so few steps carry one
-    ctx.timing_enable(max(1, min(8, args.steps // 25)))
     # a full Python garbage collection (tens of ms with torch loaded) must not land in the
     # timed region: collect now, keep the collector off while timing
     gc.collect()
     gc.disable()
+    # ---- pass 1: wall clock of the whole steps, nothing recorded on the stream but the work itself
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # ---- pass 2: one event per step boundary (about 3 us of stream time each): spread of the whole step
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record(stream)
+    for i in range(args.steps):
+        step()
+        marks[i + 1].record(stream)
+    torch.cuda.synchronize()
+    step_us = np.array([marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)])
+    # ---- pass 3: HIP events around every launch of each kernel, on the launch stream
+    ctx.timing_enable(1)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     timer_of_kernel = dominant
@@ -205,7 +245,8 @@ def main():
         roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                     "kernel": "append_attn_kernel", "kernel_avg_us": round(kernel_us, 2),
-                    "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2)}
+                    "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2),
+                    "flops_per_step": unit_flops}
 
     # measured streaming-read ceiling over the same pool (context for the fraction above)
     sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
@@ -227,8 +268,11 @@ def main():
     with torch.cuda.stream(stream):
         cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
+    del cal_dst
 
-    roofline["traffic"] = recorded_traffic(w, roofline["kernel"])
+    # HBM bytes per launch as rocprofv3's counters gave them when the profile summary was written
+    # (not measured by this run); null once the kernel's source has changed since
+    roofline["traffic"], roofline["traffic_source"] = recorded_traffic(w, roofline["kernel"])
     if kernel_samples.size:
         # spread of the timed launches of that kernel (the roofline uses their mean)
         p10, p50, p90 = np.percentile(kernel_samples.astype(np.float64), [10, 50, 90])
@@ -237,6 +281,21 @@ def main():
     extra = {}
     if bound == "hbm":
         roofline["frac_of_stream_read_ceiling"] = round(roofline["achieved"] / stream_gbps, 4)
+    if kind == "decode":
+        # The arithmetic next to the bytes: per context token and kv head the step does 4*d*G flops
+        # (logits and P.V for the G query heads of the group) on 4*d bytes of K and V, G flops per byte.
+        # Time the plain vector ALUs would need at their published rate, next to the time HBM needs.
+        G = w.n_q_heads // w.n_kv_heads
+        flops = (private_bytes if shared else unit_bytes) * G
+        extra["alu_ceiling"] = {
+            "flops_per_step": flops, "flops_per_kv_byte": G,
+            "us_at_hbm_peak": round(unit_bytes / HBM_PEAK_GBPS * 1e-3, 1),
+            "us_at_fp32_vector_peak": round(flops / FP32_VECTOR_PEAK_TFLOPS * 1e-6, 1),
+            "us_at_fp32_fma_unpacked_peak": round(flops / FP32_FMA_PEAK_TFLOPS * 1e-6, 1),
+            "fp32_vector_peak_TFLOPs": FP32_VECTOR_PEAK_TFLOPS, "fp32_fma_unpacked_peak_TFLOPs": FP32_FMA_PEAK_TFLOPS,
+            "achieved_TFLOPs": round(flops / (kernel_us * 1e-6) / 1e12, 1),
+            "note": "logits and P.V use two-way bf16 dot instructions (vector-peak rate) or, for "
+                    "narrow_attn_kernel, the matrix cores; packed fp32 instructions are compiled out"}
     if kind == "decode" and not shared:
         # bytes the step moves besides K/V, left out of the rate (listed so that the omission can be judged)
         plan = ctx.plan_decode(lens)
@@ -257,10 +316,11 @@ def main():
             ctx.attn_decode(lens, case["row_off"], row_off, block_ids, q, out, None, k_row, v_row, stream=stream)
         torch.cuda.synchronize()
         plain_us = (time.perf_counter() - t2) * 1e6 / 20
-        extra = {"kv_bytes_if_every_trajectory_read_its_own": logical_bytes,
-                 "plain_decode_us_per_step": round(plain_us, 1),
-                 "speedup_over_plain_decode": round(plain_us / (ms_per_step * 1e3), 3)}
+        extra.update({"kv_bytes_if_every_trajectory_read_its_own": logical_bytes,
+                      "plain_decode_us_per_step": round(plain_us, 1),
+                      "speedup_over_plain_decode": round(plain_us / (ms_per_step * 1e3), 3)})
 
+    sp10, sp50, sp90 = np.percentile(step_us, [10, 50, 90])
     result = {
         "metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -271,15 +331,24 @@ def main():
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "kv_bytes_per_step": unit_bytes, "tokens": int(np.asarray(case["lens"], dtype=np.int64).sum())},
         "us_per_step": round(ms_per_step * 1e3, 1),
+        # pass 2: one event per step boundary; these intervals include that event's stream time
+        "step_us_p10_p50_p90": [round(float(sp10), 1), round(float(sp50), 1), round(float(sp90), 1)],
         "frac_of_hbm_peak_whole_step": round(unit_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "stream_read_ceiling_GBps": round(stream_gbps, 1),
         "roofline": roofline,
         **extra,
     }
+    if kind == "append":
+        result["frac_of_mfma_peak_whole_step"] = round(unit_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case, w, np, kind, unit)
-    print(json.dumps(result))
+        result["cpu_baseline"] = cpu_baseline(case, w, np, kind, unit, cpu_budget_s)
+    # give the device memory back before the next workload is built
+    ctx.close()
+    del pool, q, out, row_off, block_ids, case
+    gc.collect()
+    torch.cuda.empty_cache()
+    return result
 
 
 def run_placement(args, np, torch, hw, heddle):
@@ -393,19 +462,22 @@ def recorded_traffic(w, kernel):
     import re
     path = os.path.join(ROOT, "profiles", f"{kernel}__{w.name}.md")
     src = os.path.join(ROOT, "paper_2603_28101_amd", "csrc", KERNEL_SOURCES[kernel])
+    source = f"profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, recorded there)"
     try:
         text = open(path).read()
         digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
     except OSError:
-        return None
+        return None, None
     m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", text)
     h = re.search(r"kernel_source_sha256\s*=\s*([0-9a-f]{64})", text)
-    if not m or not h or h.group(1) != digest:
-        return None
-    return int(m.group(1))
+    if not m or not h:
+        return None, None
+    if h.group(1) != digest:
+        return None, source + "; the kernel source has changed since, so the record does not apply"
+    return int(m.group(1)), source
 
 
-def cpu_baseline(case, w, np, kind, unit):
+def cpu_baseline(case, w, np, kind, unit, budget_s=20.0):
     """The oracle as it stands, timed on this host on a bounded sample."""
     from oracle import attention as oa
     try:
@@ -413,7 +485,6 @@ def cpu_baseline(case, w, np, kind, unit):
         blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         blas_threads = 1
-    budget_s = 20.0
     t0 = time.perf_counter()
     if kind == "pack":
         lens = (case["lens"].astype(np.int64) + (case["chunk_lens"] if "chunk_lens" in case else 0))
