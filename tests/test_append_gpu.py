@@ -185,26 +185,53 @@ def test_append_rejects_bad_arguments():
     assert_close(out, oracle_append(c)[1])
 
 
-def test_full_size_append_workload_sampled():
-    c = hw.make_workload(5, 0, threads=16)
-    w = c["workload"]
-    print(f"append workload: pool {c['pool'].nbytes / 1e9:.2f} GB, context {int(c['lens'].sum())}, "
-          f"chunk rows {int(c['chunk_lens'].sum())}", flush=True)
-    dc = DeviceCase(c)
-    out, lse = dc.append()
+_FULL_APPEND = {}
+
+
+def full_size_append(seed):
+    """Workload 5 of that seed appended on the GPU once (default plan, the launch configuration the
+    benchmark times); the comparisons below share the result.  Only the latest seed is kept."""
+    if seed not in _FULL_APPEND:
+        _FULL_APPEND.clear()
+        c = hw.make_workload(5, seed, threads=16)
+        print(f"append workload seed {seed}: pool {c['pool'].nbytes / 1e9:.2f} GB, context {int(c['lens'].sum())}, "
+              f"chunk rows {int(c['chunk_lens'].sum())}", flush=True)
+        dc = DeviceCase(c)
+        out, lse = dc.append()
+        _FULL_APPEND[seed] = (c, out, lse, dc.pool_bits())
+    return _FULL_APPEND[seed]
+
+
+@pytest.mark.parametrize("seed,part", [(s, p) for s in (0, 1) for p in range(4)])
+def test_full_size_append_workload_row_subset(seed, part):
+    """The tool-output append workload at full size.  The whole oracle is minutes of float64 work,
+    so it evaluates a fixed subset of chunk rows: rows 0, 1, C-2, C-1 and every 17th row of every
+    trajectory, all query heads (every trajectory, every kv head, the causal edge at both ends of each
+    chunk, rows of every 128-row tile).  The trajectories are spread over four test cases (b % 4) so
+    that no case computes for minutes.  Every chunk of this workload has at least 64 rows, so all
+    tiles run in the 128-row kernel, which divides by the unrounded weight sum: the derived bound is
+    the one for weights perturbed in the numerator only."""
+    c, out, lse, pool_after = full_size_append(seed)
     assert np.isfinite(out).all() and np.isfinite(lse).all()
     cu = c["cu_chunk"]
-    rng = np.random.default_rng(5)
+    assert int(c["chunk_lens"].min()) >= 64
     rows = []
-    for b in [int(np.argmax(c["lens"])), int(np.argmin(c["lens"])), int(rng.integers(0, 32))]:
+    for b in range(part, len(c["lens"]), 4):
         C = int(cu[b + 1] - cu[b])
-        rows += [int(cu[b]) + r for r in sorted({0, 1, C // 2, C - 2, C - 1, 31, 32})if 0 <= r < C]
-    rows = sorted(set(rows))
-    pool, ref, ref_lse, spread = oracle_append(c, rows=rows)
+        rows += [int(cu[b]) + r for r in sorted({0, 1, C - 2, C - 1} | set(range(0, C, 17))) if 0 <= r < C]
+    pool = c["pool"].copy()
+    ref, ref_lse, spread = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"],
+                                     c["k_new"], c["v_new"], c["n_kv_heads"], rows=rows, with_spread=True,
+                                     centered=False)
+    print(f"append workload seed {seed} part {part}: {len(rows)} rows x {c['n_q_heads']} heads compared, "
+          f"max |err| {np.abs(out[rows] - ref[rows]).max():.3e}", flush=True)
     assert_close(out[rows], ref[rows], "append workload", spread[rows])
     assert_lse_close(lse[rows], ref_lse[rows], "append workload lse")
-    # the whole chunk is in the pool, bit for bit, and nothing else changed
-    assert np.array_equal(dc.pool_bits(), pool)
+    if part == 0:
+        # the whole chunk is in the pool, bit for bit, and nothing else changed
+        assert np.array_equal(pool_after, pool)
+    if part == 3:
+        _FULL_APPEND.clear()
 
 
 # ------------------------------------------------------------------ small batches: split-K over the keys

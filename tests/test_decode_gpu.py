@@ -173,30 +173,23 @@ def test_back_to_back_calls_share_scratch_safely():
     assert_close(d_big.decode()[0], ref_big, "big again", sp_big)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 9])
-def test_full_size_workloads_sampled(cfg):
+@pytest.mark.parametrize("cfg,seed", [(2, 0), (2, 1), (3, 0), (4, 0), (9, 0)])
+def test_full_size_workloads_every_row(cfg, seed):
     """The named workloads at full size, in the launch configuration the benchmark times
-    (default plan).  The oracle evaluates sampled (trajectory, head) pairs."""
-    c = hw.make_workload(cfg, 0, threads=16)
+    (default plan): every (trajectory, query head) output row and every LSE is compared with the
+    oracle, so a wrong (item, kv head) anywhere in the plan of the full-size batch shows."""
+    c = hw.make_workload(cfg, seed, threads=16)
     w = c["workload"]
-    print(f"workload {cfg}: pool {c['pool'].nbytes / 1e9:.2f} GB, tokens {int(c['lens'].sum())}", flush=True)
+    print(f"workload {cfg} seed {seed}: pool {c['pool'].nbytes / 1e9:.2f} GB, tokens {int(c['lens'].sum())}", flush=True)
     dc = DeviceCase(c)
     out, lse = dc.decode()
     assert np.isfinite(out).all() and np.isfinite(lse).all()
-    lens = c["lens"]
-    order = np.argsort(lens)
-    rng = np.random.default_rng(cfg)
-    picks = {int(order[-1]), int(order[-2]), int(order[0]), int(order[len(order) // 2])}
-    picks |= set(int(x) for x in rng.choice(len(lens), 4, replace=False))
-    pairs = [(b, int(j)) for b in sorted(picks) for j in rng.choice(w.n_q_heads, 3, replace=False)]
-    ref, ref_lse, spread = oa.decode_rows(c["pool"], c["row_off"], c["block_ids"], lens, c["q"], w.n_kv_heads,
-                                          pairs, with_spread=True)
-    got = np.array([out[b, j] for b, j in pairs])
-    got_lse = np.array([lse[b, j] for b, j in pairs])
-    assert_close(got, ref, f"workload {cfg}", spread)
-    assert_lse_close(got_lse, ref_lse, f"workload {cfg} lse")
-    # property that holds at any size: sum_t w_t = 1, so |out| never exceeds max |V| (~6 for N(0,1) draws)
-    assert np.abs(out).max() < 8.0
+    ref, ref_lse, spread = oracle_decode(c)
+    assert ref.shape == (w.B, w.n_q_heads, w.head_dim)
+    print(f"workload {cfg} seed {seed}: {w.B * w.n_q_heads} rows compared, max |err| {np.abs(out - ref).max():.3e}, "
+          f"max |lse err| {np.abs(lse - ref_lse).max():.3e}", flush=True)
+    assert_close(out, ref, f"workload {cfg} seed {seed}", spread)
+    assert_lse_close(lse, ref_lse, f"workload {cfg} seed {seed} lse")
 
 
 def test_maximum_context_single_trajectory():
@@ -416,14 +409,19 @@ def test_one_context_serves_a_pool_per_layer():
 
 def test_table_entries_past_the_needed_blocks_are_never_read():
     """A table row may be longer than its trajectory needs (blocks reserved ahead, or stale entries):
-    what stands behind the needed blocks, here -1, INT32_MAX and an id just past the pool, is never
-    used as an address.  Decode, shared-prefix decode and append give the bits of the exact table."""
+    what stands behind the needed blocks is never used as an address.  The padding names blocks of
+    the pool that no trajectory owns and that are filled with NaN and Inf patterns: a stray read of
+    one shows as a bit difference in the output, a stray write as a difference in the pool.  Decode,
+    shared-prefix decode and append give the bits of the exact table.  (That ids outside the pool
+    behind the needed blocks never reach a work item is checked on the host, without a GPU.)"""
     torch = torch_mod()
     group_of = [0, 0, 0, -1, -1]
     lens = np.array([330, 500, 421, 17, 2100], dtype=np.int32)
     c = hw.build_case(entropy=[0, 61], lens=lens, n_q_heads=8, n_kv_heads=2, head_dim=128, threads=4,
                       group_of=np.asarray(group_of), shared_blocks=np.asarray([20]))
-    junk = [-1, 2 ** 31 - 1, c["n_blocks"], -(2 ** 31)]
+    owned = set(int(x) for x in c["block_ids"])
+    junk = [i for i in range(c["n_blocks"]) if i not in owned][:4]       # poisoned by the generator
+    assert len(junk) == 4 and not np.isfinite(bits_to_f64(c["pool"][junk])).any()
     rows = [list(c["block_ids"][c["row_off"][b]:c["row_off"][b + 1]]) for b in range(5)]
     need = [-(-int(n) // 16) for n in lens]
     padded = [r[:n] + junk[: 1 + b % 4] for b, (r, n) in enumerate(zip(rows, need))]

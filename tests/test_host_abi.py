@@ -246,6 +246,41 @@ def test_shared_plan_errors():
         c.plan_decode_shared([40, 20], row_off, ids)           # table row too short
 
 
+def test_ids_outside_the_pool_behind_the_needed_blocks_never_reach_a_work_item():
+    """A table row may be longer than its trajectory needs; the entries behind the needed blocks may
+    be anything (-1, INT32_MAX, an id just past the pool).  The work items the library builds from
+    the lengths name logical blocks below ceil(len/16) only, and the group search compares needed
+    entries only: the plans are those of the exact table, in both the library and the oracle."""
+    from tests.test_oracle_planner import SHARED_KEYS, csr
+    lens = np.array([330, 500, 421, 17, 2100], dtype=np.int32)
+    need = [-(-int(n) // 16) for n in lens]
+    prompt = list(range(100, 120))                        # trajectories 0-2 share 20 blocks
+    nxt = iter(range(200, 1000))
+    rows = [(prompt if b < 3 else []) + [next(nxt) for _ in range(need[b] - (20 if b < 3 else 0))] for b in range(5)]
+    junk = [-1, 2 ** 31 - 1, 1000, -(2 ** 31)]
+    padded = [r + junk[: 1 + b % 4] for b, r in enumerate(rows)]
+    for G in (4, 5):
+        c = heddle.Context(2 * G, 2, 128, 1000, n_cu=8)
+        exact_off, exact_ids = csr(rows)
+        pad_off, pad_ids = csr(padded)
+        exact = c.plan_decode_shared(lens, exact_off, exact_ids)
+        dirty = c.plan_decode_shared(lens, pad_off, pad_ids)
+        assert exact["n_groups"] == 1 and dirty["n_groups"] == 1
+        for k in SHARED_KEYS:
+            assert np.array_equal(exact[k], dirty[k]), k
+        assert (dirty["item_blk_end"] <= np.asarray(need)[dirty["item_b"]]).all()
+        assert (dirty["gitem_blk_end"] <= dirty["group_prefix"][dirty["gitem_g"]]).all()
+        assert (dirty["group_prefix"] <= (lens[dirty["group_leader"]] - 1) // 16).all()
+        kw = dict(prefix_align=4) if G == 5 else {}
+        ref = op.plan_decode_shared(lens, pad_off, pad_ids, 2, 128 // G, n_cu=8, **kw)
+        for k in SHARED_KEYS:
+            assert np.array_equal(dirty[k][: len(ref[k])], ref[k]), k
+        plain = c.plan_decode(lens)
+        assert (plain["item_blk_end"] <= np.asarray(need)[plain["item_b"]]).all()
+        tiles = c.plan_append(lens - 3, np.arange(6, dtype=np.int32) * 3)
+        assert (tiles["tile_extent"] <= lens[tiles["tile_b"]]).all()
+
+
 # ------------------------------------------------------------------ placement (Sec. 5.2)
 
 def test_placement_golden_examples_on_library():

@@ -362,3 +362,80 @@ def test_weight_spread_matches_direct_perturbation():
     w1 = np.zeros(n)
     w1[3] = 1.0
     assert np.allclose(oa.weight_spread(w1, V, V[3]), 0.0)
+
+
+def _finite_difference_std(w, V, in_denominator, eps=1e-6):
+    """Root of the summed squares of d out / d delta_t at delta = 0, by finite differences, where the
+    output is sum_t w_t (1 + delta_t) V_t over a denominator that carries the perturbation of the
+    keys flagged in `in_denominator` only (the others enter it unperturbed)."""
+    n, d = V.shape
+    base = (w @ V) / w.sum()
+    J = np.zeros((n, d))
+    for t in range(n):
+        num = w.copy()
+        num[t] *= 1 + eps
+        den = w.sum() + (w[t] * eps if in_denominator[t] else 0.0)
+        J[t] = ((num @ V) / den - base) / eps
+    return np.sqrt((J ** 2).sum(axis=0))
+
+
+def test_weight_spread_numerator_only_and_mixed_modes():
+    """centered=False is the first-order standard deviation when only the numerator carries the
+    perturbed weights (the 128-row append kernel divides by the unrounded sum); centered=None bounds
+    every mixture in which some keys' perturbations reach the denominator and the others' do not
+    (a batch served by two kernels, a shared prefix next to private blocks).  Both against explicit
+    finite perturbations; the derivative of out wrt delta_t is w_t V_t without the denominator and
+    w_t (V_t - out) with it."""
+    rng = np.random.default_rng(1)
+    n, d = 29, 6
+    w = rng.random(n) ** 3           # a few large weights, many small ones
+    w /= w.sum()
+    V = rng.standard_normal((n, d)) + 0.7          # a mean away from zero separates the two modes
+    out = w @ V
+    none_in = np.zeros(n, dtype=bool)
+    all_in = np.ones(n, dtype=bool)
+    unc = oa.weight_spread(w, V, out, centered=False)
+    cen = oa.weight_spread(w, V, out, centered=True)
+    both = oa.weight_spread(w, V, out, centered=None)
+    assert np.allclose(unc, _finite_difference_std(w, V, none_in), rtol=1e-4)
+    assert np.allclose(cen, _finite_difference_std(w, V, all_in), rtol=1e-4)
+    assert not np.allclose(unc, cen, rtol=5e-2), "the two modes must differ on this input"
+    # the bound for mixtures: never below either pure mode, equal to the root of both squares, and
+    # above every mixture of keys
+    assert np.allclose(both, np.sqrt(unc ** 2 + cen ** 2), rtol=1e-12)
+    for trial in range(20):
+        mask = rng.random(n) < rng.random()
+        mixed = _finite_difference_std(w, V, mask)
+        assert (mixed <= both * (1 + 1e-4)).all(), trial
+    # the halves of a mixture add in squares: keys [0, k) with the denominator, the rest without
+    k = 11
+    mask = np.arange(n) < k
+    expect = np.sqrt((w[:k] ** 2) @ ((V[:k] - out) ** 2) + (w[k:] ** 2) @ (V[k:] ** 2))
+    assert np.allclose(_finite_difference_std(w, V, mask), expect, rtol=1e-4)
+    # a single dominant key: with the denominator the output cannot move, without it it moves by V_t
+    w1 = np.zeros(n)
+    w1[4] = 1.0
+    assert np.allclose(oa.weight_spread(w1, V, V[4], centered=False), np.abs(V[4]))
+    assert np.allclose(oa.weight_spread(w1, V, V[4], centered=None), np.abs(V[4]))
+
+
+def test_spread_reported_by_decode_and_append_is_weight_spread_of_their_weights():
+    """decode(with_spread) and append(with_spread, centered=...) hand the mode through: recompute the
+    spread of one row from attend()'s weights."""
+    c = small_case(41, [37, 5], chunk=[6, 3])
+    for centered in (True, False, None):
+        _, _, sp = oa.decode(c["pool"], c["row_off"], c["block_ids"], c["lens"], c["q"][:2], c["n_kv_heads"],
+                             with_spread=True, centered=centered)
+        K, V = oa.gather(c["pool"], c["row_off"], c["block_ids"], 0, 37)
+        G = c["n_q_heads"] // c["n_kv_heads"]
+        j = c["n_q_heads"] - 1
+        o, _, w = oa.attend(oa.bf16_bits_to_f64(c["q"][0, j]), K[j // G], V[j // G], 1.0 / np.sqrt(c["head_dim"]))
+        assert np.allclose(sp[0, j], oa.weight_spread(w, V[j // G], o, centered), rtol=1e-12)
+        pool = c["pool"].copy()
+        _, _, spa = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"], c["k_new"],
+                              c["v_new"], c["n_kv_heads"], with_spread=True, centered=centered)
+        K, V = oa.gather(pool, c["row_off"], c["block_ids"], 1, 5 + 3)
+        r = int(c["cu_chunk"][1]) + 1                      # second chunk row of trajectory 1: sees 5 + 2 keys
+        o, _, w = oa.attend(oa.bf16_bits_to_f64(c["q"][r, j]), K[j // G][:7], V[j // G][:7],
+                            1.0 / np.sqrt(c["head_dim"]))
+        assert np.allclose(spa[r, j], oa.weight_spread(w, V[j // G][:7], o, centered), rtol=1e-12)
