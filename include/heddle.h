@@ -37,16 +37,30 @@
  * Conventions.  Every function returns HEDDLE_OK (0) or a negative code; no
  * exceptions, no abort, nothing printed.  Arguments are validated before any
  * device work is enqueued, so a failing call has no device side effect.
- * Attention calls are asynchronous on the HIP stream passed in and do not
- * synchronise it, with one exception: when the library's scratch (plan image,
- * split-K partials) has to grow - on the first call, or on a call larger than
- * any before - the device is synchronised once and the scratch reallocated.
+ * Calls that take a stream are asynchronous on it and do not synchronise it.
+ * The library's scratch (plan image, split-K partials, pinned staging ring) is
+ * sized by heddle_ctx_reserve; a call that needs more than is there - no
+ * reservation was made, or the batch is larger than the reserved one -
+ * synchronises the device once and reallocates, so a serving loop reserves for
+ * its largest batch after creating the context and never meets that case.
  * Host arrays are consumed before the call returns.  Every attention call plans
  * its work on the host from the lengths it is given and uploads that plan, so a
  * call is not something to capture into a HIP graph and replay: a replay would
- * run the plan of the captured lengths.  A context
- * is not thread-safe and its attention calls must be issued on one stream at a
- * time (they share the context's scratch).
+ * run the plan of the captured lengths.
+ * A context is not thread-safe.  All its stream-taking calls (attention, pack,
+ * unpack, copy) share its scratch and are therefore ordered: a call issued on
+ * another stream than the call before it first makes its stream wait, on the
+ * device, for the work this context has enqueued on the previous stream (one
+ * event record and one stream wait; the host does not block).  Work that should
+ * overlap - staging a preempted trajectory's cache on a side stream while decode
+ * runs - uses a second context over the same pool.  A stream that a context has
+ * been used on must stay alive until the context's next call has returned or the
+ * context is destroyed.
+ * Device pointers of queries, outputs, K/V rows, staging buffers and the pool must
+ * be 16-byte aligned (else HEDDLE_E_INVAL).  Block ids in the needed part of a
+ * device table are trusted: the library cannot see them; where it is also given
+ * the host copy (heddle_attn_decode_shared, pack, unpack, copy) ids outside the
+ * pool are HEDDLE_E_INVAL.
  */
 #ifndef HEDDLE_H
 #define HEDDLE_H
@@ -108,6 +122,16 @@ int heddle_ctx_destroy(heddle_ctx* ctx);
  * Calls already enqueued keep the pool they were issued with.  NULL or a
  * host-only context -> INVAL. */
 int heddle_ctx_set_kv_pool(heddle_ctx* ctx, void* kv_pool);
+/* Sizes the context's scratch for batches of up to max_trajectories trajectories in a
+ * decode step and, if max_chunk_rows > 0, appends of up to max_chunk_rows chunk rows in
+ * total over at most max_trajectories trajectories; with_shared_prefix != 0 also covers
+ * heddle_attn_decode_shared (a partial slot per member and prefix part: more memory).
+ * The sizes are upper bounds derived from the plan rules, so no call within these limits
+ * allocates or synchronises.  May synchronise the device itself (it replaces buffers that
+ * enqueued work may still read): call it after creation or between steps, not inside one.
+ * Never shrinks.  Errors: max_trajectories < 1, max_chunk_rows < 0 -> INVAL; host-only
+ * context -> UNSUPPORTED; allocation failure -> NOMEM. */
+int heddle_ctx_reserve(heddle_ctx* ctx, int32_t max_trajectories, int32_t max_chunk_rows, int32_t with_shared_prefix);
 
 /* ---- block manager of the paged pool (host only, O(n), all-or-nothing) ----
  * A trajectory's blocks stay allocated across tool calls and preemption
@@ -376,32 +400,6 @@ int heddle_interference_table(int32_t n_prof, const double* batch_sizes, const d
  * *time_out = total time in the profile's unit. */
 int heddle_simulate_group(int32_t n, const int32_t* lengths, int32_t n_prof, const double* batch_sizes,
                           const double* step_time, double* time_out);
-
-/* ---- measurement aids ---------------------------------------------------------
- * Average duration in microseconds of the dominant kernel of the last
- * `heddle_attn_decode` / `heddle_attn_append` calls, measured with HIP events
- * recorded on the caller's stream around that kernel.  Recording is off by
- * default; heddle_timing_enable(ctx, N) with N >= 1 clears the statistics and
- * records every N-th launch of each kernel (each recorded launch costs two
- * event records, a few microseconds of stream time); 0 turns it off.
- * heddle_timing_read synchronises the recorded events.  which: 0 = split-K
- * decode kernel, 1 = combine kernel, 2 = append attention kernel, 3 = KV write of an
- * append (a decode step's new rows are stored by the launch that uploads its plan),
- * 4 = pack, 5 = unpack, 6 = shared-prefix kernel, 7 = matrix-core kernel for tiles of few rows
- * (short chunks; decode with 8 query heads per kv head or a number of them the
- * split-K kernel is not built for). */
-int heddle_timing_enable(heddle_ctx* ctx, int32_t on);
-int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* n_launches);
-/* The recorded launches one by one: writes the durations (microseconds) of up to
- * `cap` of them to us_out (HOST, in no particular order once more than 2048 were
- * recorded and old ones overwritten) and the number held to *n_out; cap = 0
- * only counts.  Synchronises the recorded events. */
-int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us_out, int64_t* n_out);
-
-/* Streams `bytes` bytes from `src` (DEVICE) through a plain coalesced read kernel
- * and writes one checksum word per workgroup to `sink` (DEVICE, >= 4096 uint32);
- * used to measure the streaming-read ceiling of the device. */
-int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream);
 
 const char* heddle_strerror(int code);
 /* Text of the HIP call that made the calling thread's last HEDDLE_E_HIP, or of the limit that its

@@ -106,6 +106,7 @@ class AppendArgs(C.Structure):
 
 lib.heddle_ctx_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
 lib.heddle_ctx_destroy.argtypes = [vp]
+lib.heddle_ctx_reserve.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32]
 lib.heddle_kv_alloc.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_free.argtypes = [vp, C.c_int32, i32p]
 lib.heddle_kv_retain.argtypes = [vp, C.c_int32, i32p]
@@ -135,7 +136,7 @@ lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
-for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_set_kv_pool", "heddle_kv_alloc", "heddle_kv_free",
+for _f in ("heddle_ctx_create", "heddle_ctx_destroy", "heddle_ctx_reserve", "heddle_ctx_set_kv_pool", "heddle_kv_alloc", "heddle_kv_free",
            "heddle_kv_retain",
            "heddle_kv_num_free", "heddle_plan_decode", "heddle_plan_append", "heddle_attn_decode",
            "heddle_attn_decode_static",
@@ -269,6 +270,11 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def reserve(self, max_trajectories: int, max_chunk_rows: int = 0, with_shared_prefix: bool = False) -> None:
+        """Sizes the scratch for the largest batch: no later call within these limits allocates or synchronises."""
+        _check(lib.heddle_ctx_reserve(self._h, int(max_trajectories), int(max_chunk_rows), 1 if with_shared_prefix else 0),
+               "heddle_ctx_reserve")
 
     def set_kv_pool(self, kv_pool) -> None:
         """Another pool of the same shape (one per layer of a model); later calls read and write it."""

@@ -10,6 +10,7 @@
 #include <new>
 #include <vector>
 
+#include "heddle_debug.h"
 #include "heddle_internal.h"
 #include "kernels.h"
 
@@ -80,6 +81,10 @@ struct heddle_ctx {
   float* dev_part_ml = nullptr;
   size_t dev_part_ml_elems = 0;
   unsigned char* static_scratch = nullptr;   // this device's copy of `scratch` (nullptr: lookup failed)
+  // The scratch above serves one call after the other in stream order.  A call on another stream
+  // than the one before first waits (on the device) for that stream's work of this context.
+  hipStream_t last_stream = nullptr;
+  hipEvent_t handoff = nullptr;
 
   int32_t timing_every = 0;             // 0 = off; N = record every N-th launch of each kernel
   KernelTimer timers[kTimedKernels];
@@ -203,6 +208,20 @@ int upload(heddle_ctx* ctx, StagingSlot* s, size_t words, hipStream_t stream, co
   return upload_to(ctx, s, words, ctx->dev_plan, stream, rows);
 }
 
+// Every stream-taking call passes here before it touches the staging ring or the scratch: work of
+// this context already enqueued on another stream is ordered in front of what the call enqueues.
+int enter_stream(heddle_ctx* ctx, hipStream_t stream) {
+  if (ctx->enqueued && stream != ctx->last_stream) {
+    HEDDLE_HIP(hipEventRecord(ctx->handoff, ctx->last_stream));
+    HEDDLE_HIP(hipStreamWaitEvent(stream, ctx->handoff, 0));
+  }
+  ctx->last_stream = stream;
+  return HEDDLE_OK;
+}
+
+// The kernels move K/V, queries and outputs in 16-byte pieces.
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
 // Address of `scratch` on the current device, asked once per device and kept.
 std::mutex g_static_mutex;
 unsigned char* g_static_ptr[kMaxDevices] = {};
@@ -253,6 +272,7 @@ void release_device_objects(heddle_ctx* ctx) {
     if (s.host) (void)hipHostFree(s.host);
   for (UploadGuard& g : ctx->guards)
     if (g.done) (void)hipEventDestroy(g.done);
+  if (ctx->handoff) (void)hipEventDestroy(ctx->handoff);
   if (ctx->dev_plan) (void)hipFree(ctx->dev_plan);
   if (ctx->dev_part_acc) (void)hipFree(ctx->dev_part_acc);
   if (ctx->dev_part_ml) (void)hipFree(ctx->dev_part_ml);
@@ -315,6 +335,14 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
         return hip_failed(e, "hipEventCreateWithFlags", __LINE__);
       }
     }
+    {
+      const hipError_t e = hipEventCreateWithFlags(&ctx->handoff, hipEventDisableTiming);
+      if (e != hipSuccess) {
+        ctx->handoff = nullptr;
+        release_device_objects(ctx.get());
+        return hip_failed(e, "hipEventCreateWithFlags", __LINE__);
+      }
+    }
     // every staging slot starts large enough for the biggest plan image the static-scratch entry
     // point accepts, which then never meets a slot it would have to enlarge
     for (StagingSlot& sl : ctx->staging) {
@@ -362,6 +390,70 @@ int heddle_ctx_destroy(heddle_ctx* ctx) {
   }
   delete ctx;
   return rc;
+}
+
+int heddle_ctx_reserve(heddle_ctx* ctx, int32_t max_trajectories, int32_t max_chunk_rows, int32_t with_shared_prefix) {
+  if (ctx == nullptr || max_trajectories < 1 || max_chunk_rows < 0) return HEDDLE_E_INVAL;
+  if (!ctx->has_device) return HEDDLE_E_UNSUPPORTED;
+  DeviceGuard guard(ctx->cfg.device);
+  if (!guard.ok()) return HEDDLE_E_HIP;
+  // Upper bounds that follow from the plan rules: a trajectory (tile) of n blocks (steps) is cut
+  // into at most n/chunk + 1 parts and chunk >= total/target, so a batch has at most
+  // target + (number of trajectories or tiles) work items.
+  const size_t B = static_cast<size_t>(max_trajectories);
+  const size_t n_kv = static_cast<size_t>(ctx->cfg.n_kv_heads);
+  const size_t Hq = static_cast<size_t>(ctx->cfg.n_q_heads), D = static_cast<size_t>(ctx->cfg.head_dim);
+  const size_t n_cu = static_cast<size_t>(ctx->plan.n_cu);
+  const size_t target = std::max<size_t>(1, n_cu * ctx->plan.wg_per_cu / n_kv);
+  size_t items = target + B, parts = target + B;
+  size_t words = 8 * items + 4 * B + 1;
+  if (with_shared_prefix) {
+    const size_t target_g = std::max<size_t>(1, n_cu * ctx->group_wg_per_cu / n_kv);
+    const size_t prefix_parts = std::min<size_t>(static_cast<size_t>(ctx->plan.max_split), target_g + 1);
+    parts += B * prefix_parts;                          // every member owns a slot per part of its group's prefix
+    words = 8 * items + 8 * (target_g + B) + 5 * B + 1 + B;
+  }
+  if (max_chunk_rows > 0) {
+    const size_t G = Hq / n_kv;
+    const size_t tile_rows = static_cast<size_t>(std::max(1, append_tile_rows(static_cast<int32_t>(G))));
+    const size_t target_a = std::max<size_t>(1, n_cu * ctx->append_wg_per_cu / n_kv);
+    const size_t tiles = static_cast<size_t>(max_chunk_rows) / tile_rows + B;
+    const size_t a_items = target_a + tiles;
+    const size_t a_slots = tile_rows * 2 * target_a;    // at most target_a tiles are cut, into at most 2 target_a parts
+    const size_t a_split_rows = tile_rows * target_a;
+    parts = std::max(parts, a_slots);
+    words = std::max(words, 8 * a_items + 3 * B + 2 + 3 * a_split_rows);
+  }
+  int rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, parts * Hq * D,
+                       sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, parts * Hq * 4, sizeof(float));
+  if (rc != HEDDLE_OK) return rc;
+  const size_t padded = (words + 3) & ~size_t{3};
+  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
+  if (rc != HEDDLE_OK) return rc;
+  bool synced = false;
+  for (StagingSlot& sl : ctx->staging) {
+    if (sl.cap_words >= padded) continue;
+    if (!synced) {                                      // a pending copy may still read the old buffers
+      HEDDLE_HIP(hipDeviceSynchronize());
+      synced = true;
+    }
+    if (sl.host != nullptr) HEDDLE_HIP(hipHostFree(sl.host));
+    sl.host = nullptr;
+    sl.host_dev = nullptr;
+    sl.cap_words = 0;
+    sl.used_at = 0;
+    void* p = nullptr;
+    if (hipHostMalloc(&p, padded * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) return HEDDLE_E_NOMEM;
+    sl.host = static_cast<int32_t*>(p);
+    sl.cap_words = padded;
+    HEDDLE_HIP(hipHostGetDevicePointer(&sl.host_dev, p, 0));
+  }
+  ctx->items.reserve(items);
+  ctx->nsplit.reserve(B);
+  ctx->part_off.reserve(B + 1);
+  return HEDDLE_OK;
 }
 
 int heddle_kv_alloc(heddle_ctx* ctx, int32_t n, int32_t* out_block_ids) {
@@ -452,6 +544,9 @@ int check_decode_args(const heddle_ctx* ctx, const heddle_decode_args* args) {
       !args->out)
     return HEDDLE_E_INVAL;
   if ((args->k_new == nullptr) != (args->v_new == nullptr)) return HEDDLE_E_INVAL;
+  if (misaligned(args->q) || misaligned(args->out) || misaligned(args->k_new) || misaligned(args->v_new) ||
+      misaligned(ctx->cfg.kv_pool))
+    return HEDDLE_E_INVAL;
   if (args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
   for (int32_t b = 0; b < B; ++b) {
     const int32_t n = args->len_host[b];
@@ -547,6 +642,13 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   if (rc != HEDDLE_OK) return rc;
   if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
   const int32_t B = args->B;
+  // the host copy of the table is at hand here: ids of the needed blocks must name pool blocks
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t* row = block_ids_host + args->row_off_host[b];
+    const int32_t need = (args->len_host[b] + HEDDLE_BLOCK_TOKENS - 1) / HEDDLE_BLOCK_TOKENS;
+    for (int32_t i = 0; i < need; ++i)
+      if (row[i] < 0 || row[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
+  }
   const bool mfma_private = private_on_matrix_cores(ctx);
 
   DeviceGuard guard(ctx->cfg.device);
@@ -569,6 +671,8 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   // plan image: item records | group item records | trajectory records | first_pos[B] | cu_rows[B+1] | members
   const size_t nB = static_cast<size_t>(B);
   const size_t words = 8 * n_items + 8 * n_gitems + 2 * nB + nB + nB + 1 + n_members;
+  rc = enter_stream(ctx, stream);
+  if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
@@ -819,6 +923,8 @@ int decode_step(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_strea
     part_acc = ctx->dev_part_acc;
     part_ml = ctx->dev_part_ml;
   }
+  rc = enter_stream(ctx, stream);
+  if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot, !static_scratch);
   if (rc != HEDDLE_OK) return rc;
@@ -945,6 +1051,9 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
       !args->block_ids || !args->q || !args->out)
     return HEDDLE_E_INVAL;
   if ((args->k == nullptr) != (args->v == nullptr)) return HEDDLE_E_INVAL;
+  if (misaligned(args->q) || misaligned(args->out) || misaligned(args->k) || misaligned(args->v) ||
+      misaligned(ctx->cfg.kv_pool))
+    return HEDDLE_E_INVAL;
   if (args->cu_chunk_host[0] != 0 || args->row_off_host[0] < 0) return HEDDLE_E_INVAL;
   for (int32_t b = 0; b < B; ++b) {
     const int64_t C = static_cast<int64_t>(args->cu_chunk_host[b + 1]) - args->cu_chunk_host[b];
@@ -985,6 +1094,8 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
 
   // plan image: item records | ctx_len[B] | cu_chunk[B+1] | cu_wblk[B+1] | records of the split rows | their row numbers
   const size_t words = 8 * n_items + 3 * static_cast<size_t>(B) + 2 + 3 * n_split_rows;
+  rc = enter_stream(ctx, stream);
+  if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
   rc = acquire_slot(ctx, words, &slot);
   if (rc != HEDDLE_OK) return rc;
@@ -1118,6 +1229,7 @@ int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hi
 static int kv_move(heddle_ctx* ctx, bool pack, int32_t n, const int32_t* block_ids_host, void* staging,
                    void* hip_stream) {
   if (ctx == nullptr || n < 0 || (n > 0 && (block_ids_host == nullptr || staging == nullptr))) return HEDDLE_E_INVAL;
+  if (misaligned(staging) || misaligned(ctx->cfg.kv_pool)) return HEDDLE_E_INVAL;
   const int64_t block_bytes =
       static_cast<int64_t>(ctx->cfg.n_kv_heads) * 2 * HEDDLE_BLOCK_TOKENS * ctx->cfg.head_dim * 2;
   for (int32_t i = 0; i < n; ++i)
@@ -1132,8 +1244,10 @@ static int kv_move(heddle_ctx* ctx, bool pack, int32_t n, const int32_t* block_i
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_stream(ctx, stream);
+  if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
-  int rc = acquire_slot(ctx, static_cast<size_t>(n), &slot);
+  rc = acquire_slot(ctx, static_cast<size_t>(n), &slot);
   if (rc != HEDDLE_OK) return rc;
   std::memcpy(slot->host, block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
   rc = upload(ctx, slot, static_cast<size_t>(n), stream);
@@ -1175,8 +1289,10 @@ int heddle_kv_copy(heddle_ctx* ctx, int32_t n, const int32_t* src_block_ids_host
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_stream(ctx, stream);
+  if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
-  int rc = acquire_slot(ctx, 2 * static_cast<size_t>(n), &slot);
+  rc = acquire_slot(ctx, 2 * static_cast<size_t>(n), &slot);
   if (rc != HEDDLE_OK) return rc;
   std::memcpy(slot->host, src_block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));
   std::memcpy(slot->host + n, dst_block_ids_host, sizeof(int32_t) * static_cast<size_t>(n));

@@ -19,11 +19,14 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def test_library_exports_every_declared_symbol():
-    text = open(os.path.join(ROOT, "include", "heddle.h")).read()
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert headers == ["heddle.h", "heddle_debug.h"]
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in headers)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(heddle_[a-z_]+)\s*\(", text)))
     assert {"heddle_kv_alloc", "heddle_kv_free", "heddle_attn_decode", "heddle_attn_append",
-            "heddle_plan_decode", "heddle_ctx_create"} <= set(names)
+            "heddle_plan_decode", "heddle_ctx_create", "heddle_ctx_reserve", "heddle_attn_decode_static",
+            "heddle_timing_enable", "heddle_stream_read"} <= set(names)
     lib = ctypes.CDLL(heddle.lib_path())
     for n in names:
         assert hasattr(lib, n), n
