@@ -189,7 +189,7 @@ def measure(args, workload, mods, cpu_budget_s):
     gc.enable()
     kernel_us, n_launch = ctx.timing_read(dominant)
     timer_of_kernel = dominant
-    kernel_name = {0: "decode_splitk_kernel", 2: "append_attn_kernel", 4: "kv_move_kernel"}[dominant]
+    kernel_name = {0: "decode_splitk_kernel", 2: "append_dma_kernel", 4: "kv_move_kernel"}[dominant]
     if kind == "decode" and n_launch == 0:
         # with 8 query heads per kv head (or 3, 5, 6, 7 ...) the library runs decode in the matrix-core kernel
         # for short-row tiles
@@ -244,7 +244,7 @@ def measure(args, workload, mods, cpu_budget_s):
         achieved = unit_flops / (kernel_us * 1e-6) / 1e12
         roofline = {"bound": bound, "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                    "kernel": "append_attn_kernel", "kernel_avg_us": round(kernel_us, 2),
+                    "kernel": "append_dma_kernel", "kernel_avg_us": round(kernel_us, 2),
                     "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2),
                     "flops_per_step": unit_flops}
 
@@ -448,7 +448,7 @@ def run_placement(args, np, torch, hw, heddle):
     }
 
 
-KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_attn_kernel": "append_kernels.hip",
+KERNEL_SOURCES = {"decode_splitk_kernel": "decode_kernels.hip", "append_dma_kernel": "append_kernels.hip",
                   "narrow_attn_kernel": "narrow_kernels.hip",
                   "kv_move_kernel": "misc_kernels.hip"}
 
