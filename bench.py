@@ -270,6 +270,30 @@ def measure(args, workload, mods, cpu_budget_s):
     torch.cuda.synchronize()
     del cal_dst
 
+    if bound == "mfma":
+        # What the matrix cores sustain on this machine: the vendor library's bf16 GEMM (8192^3 through
+        # torch.matmul, a measurement aid, not part of the path) on N(0,1) data and on constant data.
+        # The part is power-limited under matrix-core load and draws more on data that toggles, so the
+        # published peak (2.4 GHz) is out of reach of any kernel fed with real values.
+        def gemm_tflops(make):
+            n = 8192
+            ga, gb = make(n), make(n)
+            with torch.cuda.stream(stream):
+                for _ in range(3):
+                    gc_ = ga @ gb
+                g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                g0.record(stream)
+                for _ in range(20):
+                    gc_ = ga @ gb
+                g1.record(stream)
+            torch.cuda.synchronize()
+            del gc_
+            return 2 * n ** 3 * 20 / (g0.elapsed_time(g1) * 1e-3) / 1e12
+        rand = gemm_tflops(lambda n: torch.randn(n, n, device="cuda", dtype=torch.bfloat16))
+        const = gemm_tflops(lambda n: torch.full((n, n), 0.001, device="cuda", dtype=torch.bfloat16))
+        roofline["library_gemm_bf16_TFLOPs"] = {"normal_data": round(rand, 1), "constant_data": round(const, 1)}
+        roofline["frac_of_library_gemm_normal_data"] = round(roofline["achieved"] / rand, 4)
+
     # HBM bytes per launch as rocprofv3's counters gave them when the profile summary was written
     # (not measured by this run); null once the kernel's source has changed since
     roofline["traffic"], roofline["traffic_source"] = recorded_traffic(w, roofline["kernel"])
