@@ -275,7 +275,8 @@ int heddle_attn_decode_static(heddle_ctx* ctx, const heddle_decode_args* args, v
  *     id is new leads that id; a later trajectory with the same first id joins the
  *     leader's group iff lcp >= min_share_blk, lcp = number of leading table entries
  *     equal to the leader's, capped by both shareable counts and, in a context whose
- *     G is not 1, 2, 4 or 8, rounded down to a multiple of 4.  A group exists iff
+ *     decode steps run on the matrix-core kernel (see below), rounded down to a
+ *     multiple of 4.  A group exists iff
  *     someone joined; prefix p_g = min lcp of the joined; members ascending;
  *     groups numbered by ascending leader.
  *  3. chunk from W = sum_b (nblk[b] - prefix[b]) as in heddle_plan_decode; chunk_g
@@ -308,7 +309,13 @@ int heddle_plan_decode_shared(const heddle_ctx* ctx, int32_t B, const int32_t* l
                               const int32_t* row_off_host, const int32_t* block_ids_host,
                               heddle_shared_plan* plan);
 
-/* Same arguments, results and errors as heddle_attn_decode, plus the HOST copy of
+/* Kernel routing of both decode entry points (stated here because it shows in the plan):
+ * with head_dim 128 and tile_blk a multiple of 4, contexts with 8 query heads per kv head,
+ * or with a number of them other than 1, 2, 4, 8, read the blocks of a decode step with
+ * the matrix-core kernel for short-row tiles, which starts at multiples of 64 keys; all
+ * other contexts use the packed-dot split-K kernel.
+ *
+ * Same arguments, results and errors as heddle_attn_decode, plus the HOST copy of
  * the block table (block_ids_host [row_off_host[B]], read before the call returns)
  * from which the groups are found.  Two trajectories may name the same physical
  * block only in positions wholly below both lengths. */

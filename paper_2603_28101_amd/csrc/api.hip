@@ -557,10 +557,19 @@ int check_decode_args(const heddle_ctx* ctx, const heddle_decode_args* args) {
   return HEDDLE_OK;
 }
 
-// True if this context's private blocks (and plain decode) run on the matrix-core kernel for
-// short-row tiles only: a head shape the packed-dot kernel has no lane layout for.
-bool private_on_matrix_cores(const heddle_ctx* ctx) {
-  return !decode_shape_supported(ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+// Which kernel reads the blocks of a decode step (all of them in heddle_attn_decode, the private
+// ones in heddle_attn_decode_shared): true = the matrix-core kernel for short-row tiles, fed the plan
+// as an append of one token per trajectory; false = the packed-dot split-K kernel.
+// With 8 query heads per kv head the packed-dot kernel is bound by its arithmetic and the matrix-core
+// kernel is not; head shapes the packed-dot kernel has no lane layout for (3, 5, 6, 7 ... query heads
+// per kv head) have no other choice.  The matrix-core kernel cuts keys at multiples of 64, so the
+// plan's parts must start at multiples of 4 blocks (tile_blk % 4 == 0); a context whose shape needs
+// that kernel is only created with such a tile_blk.
+bool decode_on_matrix_cores(const heddle_ctx* ctx) {
+  const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
+  const bool aligned = ctx->plan.tile_blk % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
+  const bool splitk_built = decode_shape_supported(G, ctx->cfg.head_dim);
+  return narrow_shape_supported(G, ctx->cfg.head_dim) && aligned && (G == 8 || !splitk_built);
 }
 
 // Group formation of the shared-prefix plan with this context's parameters; on shapes the
@@ -571,9 +580,10 @@ void plan_shared_for(const heddle_ctx* ctx, int32_t B, const int32_t* len, const
                      const int32_t* block_ids, SharedPlan& out) {
   const int32_t G = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
   const int32_t step_blk = kAppendStepKeys / HEDDLE_BLOCK_TOKENS;
-  const bool mfma_private = private_on_matrix_cores(ctx);
+  const bool mfma_private = decode_on_matrix_cores(ctx);
+  // a shape that needs the matrix-core kernel with a plan off its 64-key grid cannot be created
   const bool can_group = append_shape_supported(G, ctx->cfg.head_dim) &&
-                         (!mfma_private || ctx->plan.tile_blk % step_blk == 0);
+                         (mfma_private || decode_shape_supported(G, ctx->cfg.head_dim));
   const int32_t tile_members = can_group ? append_tile_rows(G) : 1;
   plan_decode_shared(ctx->plan, can_group ? ctx->min_share_blk : INT32_MAX, ctx->group_wg_per_cu, tile_members,
                      mfma_private ? step_blk : 1, B, len, row_off, block_ids, out);
@@ -649,7 +659,7 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     for (int32_t i = 0; i < need; ++i)
       if (row[i] < 0 || row[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
   }
-  const bool mfma_private = private_on_matrix_cores(ctx);
+  const bool mfma_private = decode_on_matrix_cores(ctx);
 
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;
@@ -686,7 +696,6 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   for (size_t i = 0; i < n_items; ++i) {
     const DecodeItem& it = sp.items[i];
     if (mfma_private) {       // the item as the matrix-core kernel reads it: one new token of trajectory b
-      if (it.blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) != 0) return HEDDLE_E_UNSUPPORTED;
       AppendItemRec& r = reinterpret_cast<AppendItemRec*>(w)[i];
       r.b = it.b;
       r.row0 = 0;
@@ -879,16 +888,8 @@ int decode_step(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_strea
   const size_t n_parts = static_cast<size_t>(ctx->part_off[B]);
   const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
 
-  // With 8 query heads per kv head the packed-dot kernel is bound by its arithmetic; the
-  // matrix-core kernel for short-row tiles, fed the same plan as an append of one token per
-  // trajectory, is not.  It cuts keys at multiples of 64, so every item must start there.
-  // Head shapes the packed-dot kernel is not built for (any other number of query heads per kv
-  // head up to 32, d = 128) run there too; the context was only created if its plans qualify.
-  const bool splitk_built = decode_shape_supported(Hq / ctx->cfg.n_kv_heads, D);
-  bool on_matrix_cores = (Hq / ctx->cfg.n_kv_heads == 8 || !splitk_built) && D == 128;
-  for (size_t i = 0; i < n_items && on_matrix_cores; ++i)
-    on_matrix_cores = ctx->items[i].blk_begin % (kAppendStepKeys / HEDDLE_BLOCK_TOKENS) == 0;
-  if (!on_matrix_cores && !splitk_built) return HEDDLE_E_UNSUPPORTED;
+  const bool on_matrix_cores = decode_on_matrix_cores(ctx);
+  if (!on_matrix_cores && !decode_shape_supported(Hq / ctx->cfg.n_kv_heads, D)) return HEDDLE_E_UNSUPPORTED;
 
   // plan image: item records | trajectory records | first_pos[B] | cu_rows[B+1]
   const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 2 * static_cast<size_t>(B) + 1;

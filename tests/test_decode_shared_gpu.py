@@ -50,7 +50,11 @@ def test_groups_of_every_shape(n_q, n_kv):
                dict(n_cu=8, wg_per_cu=1, min_chunk_blk=4, tile_blk=4, max_split=3)):
         dc = DeviceCase(c, **kw)
         plan = dc.ctx.plan_decode_shared(c["lens"], c["row_off"], c["block_ids"])
-        assert plan["n_groups"] == 3 and sorted(plan["group_prefix"].tolist()) == shared
+        # with 8 query heads per kv head and parts on the 4-block grid the private blocks go to the
+        # matrix-core kernel, which starts at multiples of 64 keys: shared prefixes end there
+        on_grid = n_q // n_kv == 8 and kw.get("tile_blk", 4) % 4 == 0
+        want = [p // 4 * 4 for p in shared] if on_grid else shared
+        assert plan["n_groups"] == 3 and sorted(plan["group_prefix"].tolist()) == want
         out, lse = run_shared(dc)
         assert_close(out, ref, f"shared {kw}", spread)
         assert_lse_close(lse, ref_lse, f"shared lse {kw}")
