@@ -33,6 +33,12 @@ int heddle_timing_read(heddle_ctx* ctx, int32_t which, double* avg_us, int64_t* 
  * only counts.  Synchronises the recorded events. */
 int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us_out, int64_t* n_out);
 
+/* What the context's scratch holds at the moment, in bytes: out3[0] plan buffer (device),
+ * out3[1] split-K partials (device), out3[2] pinned staging ring (host).  A value that
+ * changes between two calls means the call in between reallocated (and synchronised):
+ * after heddle_ctx_reserve no call within the reserved limits may change them. */
+int heddle_ctx_scratch_bytes(const heddle_ctx* ctx, uint64_t* out3 /* HOST [3] */);
+
 /* Streams `bytes` bytes from `src` (DEVICE) through a plain coalesced read kernel
  * and writes one checksum word per workgroup to `sink` (DEVICE, >= 4096 uint32);
  * used to measure the streaming-read ceiling of the device. */

@@ -133,6 +133,8 @@ lib.heddle_timing_enable.argtypes = [vp, C.c_int32]
 lib.heddle_timing_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.heddle_timing_samples.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
 lib.heddle_stream_read.argtypes = [vp, C.c_uint64, vp, vp]
+lib.heddle_ctx_scratch_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
+lib.heddle_ctx_scratch_bytes.restype = C.c_int
 lib.heddle_strerror.argtypes = [C.c_int]
 lib.heddle_strerror.restype = C.c_char_p
 lib.heddle_last_error_detail.restype = C.c_char_p
@@ -451,6 +453,12 @@ class Context:
         _check(lib.heddle_kv_copy(self._h, s.shape[0], sp, dp, _stream_ptr(stream)), "heddle_kv_copy")
 
     # ---- measurement
+    def scratch_bytes(self):
+        """(plan buffer, split-K partials, pinned staging ring) in bytes, as allocated right now."""
+        out = (C.c_uint64 * 3)()
+        _check(lib.heddle_ctx_scratch_bytes(self._h, out), "heddle_ctx_scratch_bytes")
+        return tuple(int(x) for x in out)
+
     def timing_enable(self, every: int = 1) -> None:
         """every = N >= 1: record every N-th launch of each kernel; 0 / False: off."""
         _check(lib.heddle_timing_enable(self._h, int(every)), "heddle_timing_enable")

@@ -1370,6 +1370,16 @@ int heddle_timing_samples(heddle_ctx* ctx, int32_t which, int64_t cap, float* us
   return HEDDLE_OK;
 }
 
+int heddle_ctx_scratch_bytes(const heddle_ctx* ctx, uint64_t* out3) {
+  if (ctx == nullptr || out3 == nullptr) return HEDDLE_E_INVAL;
+  out3[0] = ctx->dev_plan_words * sizeof(int32_t);
+  out3[1] = (ctx->dev_part_acc_elems + ctx->dev_part_ml_elems) * sizeof(float);
+  uint64_t staging = 0;
+  for (const StagingSlot& sl : ctx->staging) staging += sl.cap_words * sizeof(int32_t);
+  out3[2] = staging;
+  return HEDDLE_OK;
+}
+
 int heddle_stream_read(const void* src, uint64_t bytes, uint32_t* sink, void* hip_stream) {
   if (src == nullptr || sink == nullptr || bytes < 16) return HEDDLE_E_INVAL;
   HEDDLE_HIP(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)));

@@ -126,3 +126,51 @@ def test_misaligned_pointers_are_refused():
     ref, ref_lse, spread = oa.decode(case["pool"], case["row_off"], case["block_ids"], case["lens"], case["q"], 2,
                                      with_spread=True)
     assert_close(out, ref, "after refused calls", spread)
+
+
+def test_reserved_sizes_hold_for_random_batches_within_the_limits():
+    """heddle_ctx_reserve sizes the scratch from upper bounds of the plan rules.  Random decode,
+    shared-prefix decode and append batches within the reserved limits, under the default plan and
+    under plans forced into many parts, must leave the allocated sizes as reserve made them."""
+    torch = torch_mod()
+    rng = np.random.default_rng(77)
+    max_B, max_rows = 48, 2000
+    for kw in (dict(), dict(n_cu=64, wg_per_cu=8, min_chunk_blk=1, tile_blk=4, max_split=64, group_wg_per_cu=4,
+                            append_wg_per_cu=4, append_min_steps=1), dict(n_cu=8, max_split=3)):
+        for n_q, n_kv in ((32, 8), (16, 2), (10, 2)):
+            # one pool for all batches of this shape: 48 trajectories of up to 6000 + 300 tokens
+            # the first 40 trajectories are four groups whose members share 8, 20, 50 and 100 leading blocks
+            lens_max = np.full(max_B, 6400, dtype=np.int32)
+            group_of = np.array([b % 4 if b < 40 else -1 for b in range(max_B)])
+            shared = np.array([8, 20, 50, 100])
+            pool_case = hw.build_case(entropy=[0x58, n_q], lens=lens_max, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=128,
+                                      threads=8, poison=False, group_of=group_of, shared_blocks=shared)
+            dc = DeviceCase(pool_case, **kw)
+            dc.ctx.reserve(max_B, max_rows, with_shared_prefix=True)
+            sizes = dc.ctx.scratch_bytes()
+            qbuf = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((max_rows, n_q, 128), dtype=np.float32)))
+            kbuf = to_dev_bf16(hw.f32_to_bf16_bits(rng.standard_normal((max_rows, n_kv, 128), dtype=np.float32)))
+            obuf = torch.empty_like(qbuf)
+            for trial in range(12):
+                B = int(rng.integers(1, max_B + 1))
+                kind = trial % 3
+                if kind == 2:                                   # append: long-tailed contexts, chunks that sum to <= max_rows
+                    L = np.minimum(rng.lognormal(np.log(800), 1.2, B).astype(np.int32) + 1, 6000)
+                    C = rng.integers(1, max(2, max_rows // B), B).astype(np.int32)
+                    cu = np.concatenate([[0], np.cumsum(C)]).astype(np.int32)
+                    dc.ctx.attn_append(L, cu, pool_case["row_off"][: B + 1], dc.row_off, dc.block_ids, qbuf, kbuf, kbuf,
+                                       obuf, None)
+                else:
+                    lens = np.minimum(rng.lognormal(np.log(600), 1.5, B).astype(np.int32) + 1, 6400)
+                    if trial % 2:
+                        lens[:] = int(rng.integers(1, 6400))    # equal lengths: the most items for a given total
+                    if kind == 1:                               # long enough to use the shared blocks
+                        lens = np.maximum(lens, np.where(group_of[:B] >= 0, shared[group_of[:B]] * 16 + 1, 1)).astype(np.int32)
+                    if kind == 0:
+                        dc.ctx.attn_decode(lens, pool_case["row_off"][: B + 1], dc.row_off, dc.block_ids, qbuf, obuf)
+                    else:
+                        dc.ctx.attn_decode_shared(lens, pool_case["row_off"][: B + 1], pool_case["block_ids"], dc.row_off,
+                                                  dc.block_ids, qbuf, obuf)
+                assert dc.ctx.scratch_bytes() == sizes, (kw, n_q, n_kv, trial, kind, B)
+            torch.cuda.synchronize()
+            dc.ctx.close()
