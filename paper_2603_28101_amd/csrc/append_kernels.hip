@@ -18,21 +18,16 @@
 // n = lane % 32): its 16 accumulator registers of S^T are 16 keys of that row, so the row
 // maximum and sum are register-local except for one exchange with lane ^ 32, and the
 // C-layout of S^T is already the B-operand layout of P^T once the keys of a 16-key step are
-// matched to the A-tile rows: in the register-staged kernel the V planes hold keys
-// {0-3, 8-11 | 4-7, 12-15}; in the direct-to-LDS kernel the V planes are the natural halves
-// {0-7 | 8-15} of the pool's rows (a 16-byte load cannot split them) and the K rows are
-// assigned to A-tile rows in the matching permuted order instead.  P never moves between lanes.
+// matched to the A-tile rows: the V planes are the natural halves {0-7 | 8-15} of the pool's rows
+// (a 16-byte direct-to-LDS load cannot split them) and the K rows are assigned to A-tile rows in
+// the matching permuted order.  P never moves between lanes.
 //
 // K tiles are token-major [16][d] and V tiles are transposed [d][16] in the pool, which is
 // what the A operands want: 8 consecutive d of one key for K, 8 consecutive keys of one d
 // for V.  Both are staged through LDS (XOR-swizzled K rows, V blocks as two planes of 8 keys,
-// double buffer, one barrier per 64 keys) and shared by the four waves.  Two kernels:
-//   append_dma_kernel       head_dim 128: direct-to-LDS loads (global_load_lds_dwordx4) fill the
-//                           next stage while the current one is multiplied; no staging registers,
-//                           no LDS write instructions
-//   append_attn_kernel<64>  head_dim 64: 16-byte global loads into registers one step ahead,
-//                           written to LDS a step later (the form both head sizes used before;
-//                           kept for the head size no workload of the paper has)
+// double buffer, one barrier per 64 keys) and shared by the four waves.  The next stage is
+// filled by direct-to-LDS loads (global_load_lds_dwordx4) while the current one is multiplied:
+// no staging registers, no LDS write instructions.
 #include <type_traits>
 
 #include "kernels.h"
@@ -222,211 +217,8 @@ __device__ __forceinline__ void store_row(const Launch& a, const TileRow& t, f32
 // Launch = GroupLaunch: the decode queries of the trajectories of a group against a range of the
 // blocks they share (whole blocks, every key visible to every row), split-K partial output.
 template <int D, typename Launch>
-__global__ __launch_bounds__(256, 2) void append_attn_kernel(Launch a) {
-  static_assert(D == 128 || D == 64, "staging roles and swizzle are written for head_dim 128 and 64");
-  constexpr int NK = D / 16;             // MFMA steps over d for S^T
-  constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
-  constexpr int kTileElems = kBlockTokens * D;
-  constexpr int kStageK = kChunkTokens * D;            // elements of K per LDS stage
-  constexpr int kStageV = kChunkBlocks * kTileElems;   // elements of V per LDS stage
-  constexpr int kVPlane = D * 8;                       // elements of one 8-key plane of a V block
-
-  // Two stages (double buffer).  K rows are 2 D bytes = D/8 slots of 16 B (16 at d = 128); slot c of
-  // key row t is stored at slot c ^ (t & (D/8 - 1)), so that the 32 lanes reading the same d-slice
-  // of 32 different keys spread over the banks.  A V block is two planes of [d][8 keys]: plane 0
-  // holds keys {0-3, 8-11}, plane 1 keys {4-7, 12-15}, so that the 16 lanes an LDS read serves
-  // per cycle (consecutive head-dim rows of one plane) fall into 16 different bank groups;
-  // with [d][16 keys] rows every other row of a half collided.
-  __shared__ __attribute__((aligned(16))) uint16_t s_k[2][kStageK];
-  __shared__ __attribute__((aligned(16))) uint16_t s_v[2][kStageV];
-
-  const int tile = blockIdx.x / a.n_kv_heads;
-  const int h = blockIdx.x - tile * a.n_kv_heads;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int n = lane & 31;               // query row (column of S^T / O^T) within the wave
-  const int hi = lane >> 5;
-
-  // this lane's work item and query row (row wave*32 + n of the tile's 128)
-  const TileRow tr = read_item(a, tile, h, wave * 32 + n);
-  const int extent = tr.extent, kv_len = tr.kv_len, edge = tr.edge, pos = tr.pos;
-  const int32_t* const table = tr.table;
-
-  // Q^T operand: B[k = d][n = row], 8 consecutive d per lane and step
-  bf16x8 qb[NK];
-  {
-    const uint16_t* qp = a.q + (tr.q_row * a.n_q_heads + tr.head) * D + hi * 8;
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) qb[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + kk * 16));
-  }
-
-  f32x16 o[NMT];
-#pragma unroll
-  for (int mt = 0; mt < NMT; ++mt)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) o[mt][j] = 0.0f;
-  float m_ref = -INFINITY, l_sum = 0.0f;
-
-  const int64_t head_stride = 2 * kTileElems;
-  const int64_t block_stride = static_cast<int64_t>(a.n_kv_heads) * head_stride;
-  const int n_blocks_needed = (extent + kBlockTokens - 1) / kBlockTokens;
-  const int n_chunks = (extent + kChunkTokens - 1) / kChunkTokens;
-
-  // staging roles.  d = 128: per chunk and thread one 16-byte piece of K and one of V from each block
-  //   K piece x: key row 16x + tid/16, d slice tid%16
-  //   V piece x: block x, d row tid/2, key half tid%2 (8 keys)
-  // d = 64: a block's K tile and V tile are 128 pieces each, so waves 0-1 stage K and waves 2-3
-  // stage V, one piece per thread and block
-  //   K piece x: key row 16x + (tid%128)/8, d slice tid%8
-  //   V piece x: block x, d row (tid%128)/2, key half tid%2
-  constexpr int kSlots = D / 8;                       // 16-byte pieces of a K row
-  const bool stages_v = D == 128 || tid >= 128;       // (uniform per wave)
-  const bool stages_k = D == 128 || tid < 128;
-  const int k_tok = D == 128 ? tid >> 4 : (tid & 127) >> 3, k_slice = tid & (kSlots - 1);
-  const int v_row = D == 128 ? tid >> 1 : (tid & 127) >> 1, v_half = tid & 1;
-
-  // Physical block ids are read through the constant address space (scalar loads, the table
-  // does not change during the launch) one chunk ahead of the K/V loads that need them, so
-  // that no K/V load waits for a table lookup.
-  typedef const __attribute__((address_space(4))) int32_t* const_ids_t;
-  const const_ids_t ctable = (const_ids_t)(reinterpret_cast<uintptr_t>(table));
-  int ids[kChunkBlocks];
-  auto load_ids = [&](int c) {
-#pragma unroll
-    for (int x = 0; x < kChunkBlocks; ++x) ids[x] = ctable[min(kChunkBlocks * c + x, n_blocks_needed - 1)];
-  };
-
-  // byte offsets of this thread's pieces inside a (block, kv head) pair of tiles: with the pair's
-  // address in scalar registers a load needs no vector address arithmetic (global_load with a
-  // scalar base and a 32-bit lane offset).  The compiler picks that form only if it sees, next to
-  // the load, a base that lives in scalar registers and a lane offset that is widened there: left
-  // alone it adds the loop-invariant 64-bit lane address to the block offset with a 64-bit vector
-  // add per load, hence the two empty asm statements in fetch().
-  const uint32_t k_piece = static_cast<uint32_t>(k_tok * D + k_slice * 8) * 2u;
-  const uint32_t v_piece = D == 128 || stages_v
-                               ? static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u
-                               : k_piece;
-  const char* pool_h = reinterpret_cast<const char*>(a.pool + h * head_stride);
-
-  // d = 64: a thread stages K or V, not both; its pieces travel in stage_v, at offset v_piece
-  u32x4 stage_k[D == 128 ? kChunkBlocks : 1], stage_v[kChunkBlocks];
-  // may_pass_end: the chunk can hold slots past the cache (only the item's last chunk can)
-  auto fetch = [&](int c, auto may_pass_end) {   // uses the ids loaded by the preceding load_ids(c)
-#pragma unroll
-    for (int x = 0; x < kChunkBlocks; ++x) {
-      // a block past the item's last one repeats that block (load_ids clamps): its keys are
-      // masked as beyond every row's position, and its V pieces are cleared below
-      const int blk = kChunkBlocks * c + x;
-      typedef const __attribute__((address_space(1))) char* gptr_t;
-      typedef const __attribute__((address_space(1))) u32x4* gvec_t;
-      uint64_t base = reinterpret_cast<uint64_t>(pool_h) +
-                      static_cast<uint64_t>(ids[x]) * static_cast<uint64_t>(block_stride * 2);
-      uint32_t kp = k_piece, vp = v_piece;
-      asm("" : "+s"(base));
-      asm("" : "+v"(kp), "+v"(vp));
-      const gptr_t t = reinterpret_cast<gptr_t>(base);
-      if constexpr (D == 128) stage_k[x] = *reinterpret_cast<gvec_t>(t + kp);
-      u32x4 vv = *reinterpret_cast<gvec_t>(t + vp);
-      if (decltype(may_pass_end)::value && stages_v &&
-          kv_len - blk * kBlockTokens < kBlockTokens) {            // (uniform) block holds slots past the cache
-        const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
-        vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
-        vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
-        vv.z &= (4 < nv ? 0x0000ffffu : 0u) | (5 < nv ? 0xffff0000u : 0u);
-        vv.w &= (6 < nv ? 0x0000ffffu : 0u) | (7 < nv ? 0xffff0000u : 0u);
-      }
-      stage_v[x] = vv;
-    }
-  };
-  auto commit = [&](int st) {
-#pragma unroll
-    for (int x = 0; x < kChunkBlocks; ++x) {
-      const int row = x * kBlockTokens + k_tok;
-      uint16_t* krow = &s_k[st][row * D + ((k_slice ^ (D == 128 ? k_tok : (k_tok & (kSlots - 1)))) * 8)];
-      uint16_t* vrow = &s_v[st][x * kTileElems + v_row * 8 + v_half * 4];
-      if constexpr (D == 128) {
-        *reinterpret_cast<u32x4*>(krow) = stage_k[x];
-      } else if (stages_k) {
-        *reinterpret_cast<u32x4*>(krow) = stage_v[x];
-      }
-      if (stages_v) {
-        *reinterpret_cast<u32x2*>(vrow) = u32x2{stage_v[x].x, stage_v[x].y};                 // keys 8h+0..3 -> plane 0
-        *reinterpret_cast<u32x2*>(vrow + kVPlane) = u32x2{stage_v[x].z, stage_v[x].w};       // keys 8h+4..7 -> plane 1
-      }
-    }
-  };
-
-  load_ids(0);
-  fetch(0, std::true_type{});
-  load_ids(1);
-  commit(0);
-  if (n_chunks > 1) fetch(1, std::true_type{});
-  load_ids(2);
-  // One 64-key step.  kInterior: the step lies wholly before the causal edge of every row and at
-  // least three steps before the item's end, so it needs no mask and no test around its staging
-  // (the chunk it fetches, two steps ahead, is not the last one and has no slot past the cache):
-  // its body up to the rescale test is one straight run of code, which lets the LDS writes of the
-  // next stage, the global loads of the one after, the QK^T MFMAs and the row maximum be
-  // interleaved (a wave overlaps its own matrix and vector work well; two waves of a SIMD hardly
-  // overlap each other's).
-  auto step = [&](int c, auto interior) {
-    constexpr bool kInterior = decltype(interior)::value;
-    const int st = c & 1;
-    __syncthreads();                       // stage st is complete; nobody reads stage st^1 any more
-    if (kInterior || c + 1 < n_chunks) commit(st ^ 1);
-    if (kInterior) fetch(c + 2, std::false_type{});     // global loads fly during the math below
-    else if (c + 2 < n_chunks) fetch(c + 2, std::true_type{});
-    load_ids(c + 3);                       // clamped to the tile's last block
-
-    const int t0 = c * kChunkTokens;
-
-    // ---- S^T = K Q^T : two tiles of 32 keys x 32 rows
-    f32x16 s[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) s[u][j] = 0.0f;
-      const int row = 32 * u + n;
-#pragma unroll
-      for (int kk = 0; kk < NK; ++kk) {
-        const int slot = (2 * kk + hi) ^ (row & (kSlots - 1));   // row & 15 at d = 128
-        const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&s_k[st][row * D + slot * 8]));
-        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s[u], 0, 0, 0);
-      }
-    }
-
-    // register j of tile u is key t0 + 32u + 8*(j/4) + 4*hi + j%4 of this lane's row
-    u32x4 pw[kChunkBlocks];
-    softmax_step<NMT>(s, o, m_ref, l_sum, a.scale_log2, !kInterior && t0 + kChunkTokens - 1 > edge, t0, pos,
-                      [hi](int u, int j) { return 32 * u + 8 * (j >> 2) + 4 * hi + (j & 3); }, pw);
-
-    // ---- O^T += V^T P^T : one 16-key step per block, NMT tiles of 32 head-dim rows
-#pragma unroll
-    for (int x = 0; x < kChunkBlocks; ++x) {
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[x]);
-#pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) {
-        const bf16x8 va = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4*>(&s_v[st][x * kTileElems + hi * kVPlane + (mt * 32 + n) * 8]));
-        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[mt], 0, 0, 0);
-      }
-    }
-  };
-
-  // steps [0, n_interior) are interior; the last three steps and those that reach the edge are not
-  const int n_interior = max(0, min(n_chunks - 3, (edge + 1) / kChunkTokens));
-  int c = 0;
-  for (; c < n_interior; ++c) step(c, std::true_type{});
-  for (; c < n_chunks; ++c) step(c, std::false_type{});
-
-  store_row<D>(a, tr, o, m_ref, l_sum, hi);
-}
-
-// The same pass for head_dim 128 with K and V staged by direct-to-LDS loads.
-template <typename Launch>
 __global__ __launch_bounds__(256, 2) void append_dma_kernel(Launch a) {
-  constexpr int D = 128;
+  static_assert(D == 128 || D == 64, "staging roles and swizzle are written for head_dim 128 and 64");
   constexpr int NK = D / 16;             // MFMA steps over d for S^T
   constexpr int NMT = D / 32;            // 32-row tiles of O^T over d
   constexpr int kTileElems = kBlockTokens * D;
@@ -436,8 +228,11 @@ __global__ __launch_bounds__(256, 2) void append_dma_kernel(Launch a) {
 
   // Two stages of K and of V, each an LDS object of its own: the compiler then knows that a
   // direct-to-LDS load into one stage does not alias the operand reads of the other and does not
-  // make those reads wait for it.  K rows are 256 B = 16 slots of 16 B; slot c of key row t sits at
-  // slot c ^ (t & 15).  A V block is two planes of [d][8 keys]: plane 0 keys 0-7, plane 1 keys 8-15.
+  // make those reads wait for it.  K rows are 2 D bytes = D/8 slots of 16 B (16 at d = 128); slot c
+  // of key row t sits at slot c ^ (t & (D/8 - 1)), so that the 32 lanes reading the same d-slice of
+  // 32 different keys spread over the banks.  A V block is two planes of [d][8 keys] (plane 0 keys
+  // 0-7, plane 1 keys 8-15): the 16 lanes an LDS read serves per cycle, consecutive head-dim rows of
+  // one plane, fall into 16 different bank groups.
   __shared__ __attribute__((aligned(16))) uint16_t s_k0[kStageK];
   __shared__ __attribute__((aligned(16))) uint16_t s_k1[kStageK];
   __shared__ __attribute__((aligned(16))) uint16_t s_v0[kStageV];
@@ -478,18 +273,33 @@ __global__ __launch_bounds__(256, 2) void append_dma_kernel(Launch a) {
 
   // Staging.  A wave-level direct-to-LDS load moves 64 x 16 B from per-lane global addresses to
   // 1 KB of consecutive LDS: the swizzle of the K rows is therefore applied on the global side.
-  //   K, block x: wave w fills key rows 16x + 4w .. + 3: lane i -> row 4w + i/16 of the block,
-  //      LDS slot i%16, which holds the row's piece (i%16) ^ (row & 15)
-  //   V, block x: wave w fills plane w&1, head-dim rows 64 (w>>1) .. + 63: lane i -> row 64 (w>>1) + i
+  // A stage of K is D/8 such loads (kRowsPerLoad key rows each), a stage of V as many (one plane of
+  // 64 head-dim rows of one block each); a wave issues every fourth of them, D/32 of K and of V:
+  //   K load 4k + w: key rows kRowsPerLoad (4k + w) .. of the chunk: lane i -> row i / kSlots of them,
+  //      LDS slot i % kSlots, which holds the row's piece (i % kSlots) ^ (row & (kSlots - 1))
+  //   V load 4k + w: block (4k + w) / kLoadsPerBlock, plane and 64-row group from (4k + w) % kLoadsPerBlock
+  // d = 128: a wave's k-th loads belong to block k; d = 64: to block 2k + w/2 (uniform per wave).
+  constexpr int kSlots = D / 8;                       // 16-byte pieces of a K row
+  constexpr int kRowsPerLoad = 64 / kSlots;           // 4 or 8
+  constexpr int kLoadsPerWave = D / 32;               // of K, and of V, per stage
+  constexpr int kLoadsPerBlock = D / 32;              // of V (two planes x D/64 groups of 64 rows); of K: 16 / kRowsPerLoad
   const int wv = __builtin_amdgcn_readfirstlane(wave);
-  const int k_row_in = 4 * wv + (lane >> 4);
-  const uint32_t k_goff = static_cast<uint32_t>(k_row_in * D + (((lane & 15) ^ (k_row_in & 15)) * 8)) * 2u;
-  const uint32_t v_goff = static_cast<uint32_t>(kTileElems + (64 * (wv >> 1) + lane) * kBlockTokens + (wv & 1) * 8) * 2u;
-  const int k_loff = 4 * wv * D;                                    // elements, + x * 16 * D
-  const int v_loff = (wv & 1) * kVPlane + (wv >> 1) * 64 * 8;        // elements, + x * kTileElems
+  const int k_row_in = (kRowsPerLoad * wv) % kBlockTokens + lane / kSlots;       // row within its block
+  const uint32_t k_goff =
+      static_cast<uint32_t>(k_row_in * D + (((lane % kSlots) ^ (k_row_in & (kSlots - 1))) * 8)) * 2u;
+  const int v_within = wv % kLoadsPerBlock, v_plane = v_within & 1, v_group = v_within >> 1;
+  const uint32_t v_goff = static_cast<uint32_t>(kTileElems + (64 * v_group + lane) * kBlockTokens + v_plane * 8) * 2u;
+  // block of this wave's k-th load (the same for K and V) and the LDS offsets of the loads, in elements
+  auto load_block = [&](int k) { return D == 128 ? k : 2 * k + (wv >> 1); };
+  auto k_loff = [&](int k) { return kRowsPerLoad * (4 * k + wv) * D; };
+  auto v_loff = [&](int k) { return load_block(k) * kTileElems + v_plane * kVPlane + v_group * 64 * 8; };
   // the item's last chunk may hold slots past the cache, whose V must not reach the matrix cores
-  // (0 x NaN): that chunk's V goes through registers, is cleared there and stored with ds_write
-  const int v_row = tid >> 1, v_half = tid & 1;
+  // (0 x NaN): that chunk's V goes through registers, is cleared there and stored with ds_write:
+  // piece tid + 256 k of the chunk's 4 x 2 D pieces, i.e. block (tid + 256 k) / (2 D), head-dim row
+  // and key half from the remainder
+  constexpr int kPiecesPerBlock = 2 * D;
+  constexpr int kPiecesPerThread = kChunkBlocks * kPiecesPerBlock / 256;           // 4 or 2
+  const int v_row = (tid % kPiecesPerBlock) >> 1, v_half = tid & 1;
   const uint32_t v_piece = static_cast<uint32_t>(kTileElems + v_row * kBlockTokens + v_half * 8) * 2u;
 
   typedef const __attribute__((address_space(4))) int32_t* const_ids_t;
@@ -513,29 +323,34 @@ __global__ __launch_bounds__(256, 2) void append_dma_kernel(Launch a) {
   typedef const __attribute__((address_space(1))) u32x4* gvec_t;
   typedef __attribute__((address_space(3))) void* lvoid_t;
 
+  // block id number x of the chunk in `ids`, x uniform per wave (a constant at d = 128)
+  auto id_of = [&](int x) { return x == 0 ? ids[0] : x == 1 ? ids[1] : x == 2 ? ids[2] : ids[3]; };
+  auto block_base = [&](int x) {
+    uint64_t base = reinterpret_cast<uint64_t>(pool_h) + static_cast<uint64_t>(static_cast<uint32_t>(id_of(x))) * block_bytes;
+    asm("" : "+s"(base));                 // 32 x 32 -> 64 bits in scalar registers, next to the load
+    return reinterpret_cast<gptr_t>(base);
+  };
   // stages chunk cn (whose block ids are in `ids`) into stage STN; v_by_regs: see above
   auto stage_chunk = [&](int cn, auto stn, bool v_by_regs) {
     constexpr int STN = decltype(stn)::value;
-    uint16_t* const kdst = (STN ? s_k1 : s_k0) + k_loff;
-    uint16_t* const vdst = (STN ? s_v1 : s_v0);
-    uint64_t base[kChunkBlocks];
+    uint16_t* const kdst = STN ? s_k1 : s_k0;
+    uint16_t* const vdst = STN ? s_v1 : s_v0;
+    gptr_t base[kLoadsPerWave];
 #pragma unroll
-    for (int x = 0; x < kChunkBlocks; ++x) {
-      base[x] = reinterpret_cast<uint64_t>(pool_h) + static_cast<uint64_t>(static_cast<uint32_t>(ids[x])) * block_bytes;
-      asm("" : "+s"(base[x]));
-      __builtin_amdgcn_global_load_lds((gvoid_t)(reinterpret_cast<gptr_t>(base[x]) + k_goff),
-                                       (lvoid_t)(kdst + x * kBlockTokens * D), 16, 0, 0);
+    for (int k = 0; k < kLoadsPerWave; ++k) {
+      base[k] = block_base(load_block(k));
+      __builtin_amdgcn_global_load_lds((gvoid_t)(base[k] + k_goff), (lvoid_t)(kdst + k_loff(k)), 16, 0, 0);
     }
     if (!v_by_regs) {
 #pragma unroll
-      for (int x = 0; x < kChunkBlocks; ++x)
-        __builtin_amdgcn_global_load_lds((gvoid_t)(reinterpret_cast<gptr_t>(base[x]) + v_goff),
-                                         (lvoid_t)(vdst + v_loff + x * kTileElems), 16, 0, 0);
+      for (int k = 0; k < kLoadsPerWave; ++k)
+        __builtin_amdgcn_global_load_lds((gvoid_t)(base[k] + v_goff), (lvoid_t)(vdst + v_loff(k)), 16, 0, 0);
     } else {
 #pragma unroll
-      for (int x = 0; x < kChunkBlocks; ++x) {
+      for (int k = 0; k < kPiecesPerThread; ++k) {
+        const int x = load_block(k);                           // = (tid + 256 k) / kPiecesPerBlock, uniform per wave
         const int blk = kChunkBlocks * cn + x;
-        u32x4 vv = *reinterpret_cast<gvec_t>(reinterpret_cast<gptr_t>(base[x]) + v_piece);
+        u32x4 vv = *reinterpret_cast<gvec_t>(block_base(x) + v_piece);
         const int nv = kv_len - blk * kBlockTokens - v_half * 8;   // keys of this piece that exist; the rest may be NaN
         vv.x &= (0 < nv ? 0x0000ffffu : 0u) | (1 < nv ? 0xffff0000u : 0u);
         vv.y &= (2 < nv ? 0x0000ffffu : 0u) | (3 < nv ? 0xffff0000u : 0u);
@@ -580,7 +395,7 @@ __global__ __launch_bounds__(256, 2) void append_dma_kernel(Launch a) {
       const int row = 32 * u + my_key;
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
-        const int slot = (2 * kk + hi) ^ (my_key & 15);
+        const int slot = (2 * kk + hi) ^ (my_key & (kSlots - 1));
         const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&ks[row * D + slot * 8]));
         s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[kk], s[u], 0, 0, 0);
       }
@@ -625,9 +440,9 @@ template <typename Launch>
 hipError_t launch_t(const Launch& a, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(a.n_items) * static_cast<unsigned>(a.n_kv_heads));
   if (a.head_dim == 128)
-    hipLaunchKernelGGL((append_dma_kernel<Launch>), grid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((append_dma_kernel<128, Launch>), grid, dim3(256), 0, stream, a);
   else
-    hipLaunchKernelGGL((append_attn_kernel<64, Launch>), grid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((append_dma_kernel<64, Launch>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
