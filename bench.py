@@ -158,14 +158,38 @@ def measure(args, workload, mods, cpu_budget_s):
         dominant = 2
         bound = "mfma" if unit_flops / unit_bytes > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBPS else "hbm"
 
+    # a full Python garbage collection (tens of ms with torch loaded) must not land in the
+    # timed region: collect now, keep the collector off while timing.  It comes before all GPU work
+    # of the measurement: tens of ms of host work between warm-up and timed steps would let the GPU
+    # fall back to its idle clocks, and the first timed steps would pay for the ramp.
+    gc.collect()
+    gc.disable()
+    # measured streaming-read ceiling over the same pool (context for the roofline fraction); run
+    # ahead of the timed passes, it also brings the GPU out of its idle clocks
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    nbytes = pool.numel() * 2
+    for _ in range(3):
+        heddle.stream_read(pool, nbytes, sink, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(10):
+        heddle.stream_read(pool, nbytes, sink, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    stream_gbps = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE
+    # counters of a profiling run are scaled by
+    cal_src = pool.view(torch.int16).reshape(-1)[: 64 * 1024 * 1024]
+    cal_dst = torch.empty_like(cal_src)
+    with torch.cuda.stream(stream):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_dst
+
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    # a full Python garbage collection (tens of ms with torch loaded) must not land in the
-    # timed region: collect now, keep the collector off while timing
-    gc.collect()
-    gc.disable()
     # ---- pass 1: wall clock of the whole steps, nothing recorded on the stream but the work itself
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -247,28 +271,6 @@ def measure(args, workload, mods, cpu_budget_s):
                     "kernel": "append_dma_kernel", "kernel_avg_us": round(kernel_us, 2),
                     "launches_timed": n_launch, "kv_write_avg_us": round(aux_us, 2),
                     "flops_per_step": unit_flops}
-
-    # measured streaming-read ceiling over the same pool (context for the fraction above)
-    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
-    nbytes = pool.numel() * 2
-    for _ in range(3):
-        heddle.stream_read(pool, nbytes, sink, stream)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(10):
-        heddle.stream_read(pool, nbytes, sink, stream)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    stream_gbps = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-
-    # plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE
-    # counters of a profiling run are scaled by
-    cal_src = pool.view(torch.int16).reshape(-1)[: 64 * 1024 * 1024]
-    cal_dst = torch.empty_like(cal_src)
-    with torch.cuda.stream(stream):
-        cal_dst.copy_(cal_src)
-    torch.cuda.synchronize()
-    del cal_dst
 
     if bound == "mfma":
         # What the matrix cores sustain on this machine: the vendor library's bf16 GEMM (8192^3 through
