@@ -90,10 +90,8 @@ struct heddle_ctx {
   KernelTimer timers[kTimedKernels];
 
   // host scratch reused between calls
-  std::vector<DecodeItem> items;
-  std::vector<int32_t> nsplit, part_off;
   std::vector<AppendTile> tiles;
-  SharedPlan shared;
+  SharedPlan shared;                    // the plan of the last decode step (without groups in plain decode)
   int32_t min_share_blk = 4, group_wg_per_cu = 1;
   AppendSplit split;
   int32_t append_wg_per_cu = 2, append_min_steps = 4;
@@ -359,9 +357,9 @@ int heddle_ctx_create(const heddle_config* cfg, heddle_ctx** out) {
       }
     }
     ctx->static_scratch = static_scratch_of(cfg->device);
-    ctx->items.reserve(kStaticPlanWords / 8);
-    ctx->nsplit.reserve(kStaticPlanWords / 4);
-    ctx->part_off.reserve(kStaticPlanWords / 4 + 1);
+    ctx->shared.items.reserve(kStaticPlanWords / 8);
+    ctx->shared.nsplit.reserve(kStaticPlanWords / 4);
+    ctx->shared.part_off.reserve(kStaticPlanWords / 4 + 1);
     ctx->has_device = true;
   } else if (n_cu == 0) {
     n_cu = 256;
@@ -450,9 +448,9 @@ int heddle_ctx_reserve(heddle_ctx* ctx, int32_t max_trajectories, int32_t max_ch
     sl.cap_words = padded;
     HEDDLE_HIP(hipHostGetDevicePointer(&sl.host_dev, p, 0));
   }
-  ctx->items.reserve(items);
-  ctx->nsplit.reserve(B);
-  ctx->part_off.reserve(B + 1);
+  ctx->shared.items.reserve(items);
+  ctx->shared.nsplit.reserve(B);
+  ctx->shared.part_off.reserve(B + 1);
   return HEDDLE_OK;
 }
 
@@ -646,45 +644,83 @@ int heddle_plan_decode_shared(const heddle_ctx* ctx, int32_t B, const int32_t* l
   return HEDDLE_OK;
 }
 
-int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, const int32_t* block_ids_host,
-                              void* hip_stream) {
+namespace {
+
+// One decode step: heddle_attn_decode (block_ids_host == nullptr: no group search, the plan of
+// heddle_plan_decode), heddle_attn_decode_shared (groups from the host copy of the table) and
+// heddle_attn_decode_static (static_scratch: plan image and partials in the library's static device
+// array, nothing allocated).  Without groups the plan image and the launches of the shared-prefix
+// form reduce to those of the plain one.
+int decode_call(heddle_ctx* ctx, const heddle_decode_args* args, const int32_t* block_ids_host, void* hip_stream,
+                bool static_scratch) {
   int rc = check_decode_args(ctx, args);
   if (rc != HEDDLE_OK) return rc;
-  if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
   const int32_t B = args->B;
-  // the host copy of the table is at hand here: ids of the needed blocks must name pool blocks
-  for (int32_t b = 0; b < B; ++b) {
-    const int32_t* row = block_ids_host + args->row_off_host[b];
-    const int32_t need = (args->len_host[b] + HEDDLE_BLOCK_TOKENS - 1) / HEDDLE_BLOCK_TOKENS;
-    for (int32_t i = 0; i < need; ++i)
-      if (row[i] < 0 || row[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
+  if (block_ids_host != nullptr) {
+    // the host copy of the table is at hand here: ids of the needed blocks must name pool blocks
+    for (int32_t b = 0; b < B; ++b) {
+      const int32_t* row = block_ids_host + args->row_off_host[b];
+      const int32_t need = (args->len_host[b] + HEDDLE_BLOCK_TOKENS - 1) / HEDDLE_BLOCK_TOKENS;
+      for (int32_t i = 0; i < need; ++i)
+        if (row[i] < 0 || row[i] >= ctx->cfg.n_blocks) return HEDDLE_E_INVAL;
+    }
   }
+  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
   const bool mfma_private = decode_on_matrix_cores(ctx);
+  if (!mfma_private && !decode_shape_supported(Hq / ctx->cfg.n_kv_heads, D)) return HEDDLE_E_UNSUPPORTED;
 
   DeviceGuard guard(ctx->cfg.device);
   if (!guard.ok()) return HEDDLE_E_HIP;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
   SharedPlan& sp = ctx->shared;
-  plan_shared_for(ctx, B, args->len_host, args->row_off_host, block_ids_host, sp);
+  if (block_ids_host != nullptr) {
+    plan_shared_for(ctx, B, args->len_host, args->row_off_host, block_ids_host, sp);
+  } else {
+    sp.gitems.clear();
+    sp.members.clear();
+    plan_decode(ctx->plan, B, args->len_host, sp.items, sp.nsplit, sp.part_off, sp.chunk);
+  }
   const size_t n_items = sp.items.size(), n_gitems = sp.gitems.size(), n_members = sp.members.size();
   const size_t n_parts = static_cast<size_t>(sp.part_off[B]);
-  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
-
-  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, n_parts * Hq * D,
-                   sizeof(float));
-  if (rc != HEDDLE_OK) return rc;
-  rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, n_parts * Hq * 4,
-                   sizeof(float));
-  if (rc != HEDDLE_OK) return rc;
 
   // plan image: item records | group item records | trajectory records | first_pos[B] | cu_rows[B+1] | members
   const size_t nB = static_cast<size_t>(B);
   const size_t words = 8 * n_items + 8 * n_gitems + 2 * nB + nB + nB + 1 + n_members;
+  const size_t padded = (words + 3) & ~size_t{3};
+  const size_t acc_elems = n_parts * Hq * D, ml_elems = n_parts * Hq * 4;
+  int32_t* dev_plan = nullptr;
+  float *part_acc = nullptr, *part_ml = nullptr;
+  if (static_scratch) {
+    if (ctx->static_scratch == nullptr) {
+      std::snprintf(g_detail, sizeof(g_detail), "hipGetSymbolAddress(scratch) failed when the context was created");
+      return HEDDLE_E_HIP;
+    }
+    const size_t acc_bytes = (acc_elems * sizeof(float) + 255) & ~size_t{255};
+    if (padded > kStaticPlanWords || acc_bytes + ml_elems * sizeof(float) > kStaticPartBytes) {
+      std::snprintf(g_detail, sizeof(g_detail),
+                    "static scratch too small: plan image %zu words (limit %zu), partials %zu bytes (limit %zu)",
+                    words, kStaticPlanWords, acc_bytes + ml_elems * sizeof(float), kStaticPartBytes);
+      return HEDDLE_E_NOMEM;
+    }
+    dev_plan = reinterpret_cast<int32_t*>(ctx->static_scratch);
+    part_acc = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t));
+    part_ml = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t) + acc_bytes);
+  } else {
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, acc_elems, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, ml_elems, sizeof(float));
+    if (rc != HEDDLE_OK) return rc;
+    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, padded, sizeof(int32_t));
+    if (rc != HEDDLE_OK) return rc;
+    dev_plan = ctx->dev_plan;
+    part_acc = ctx->dev_part_acc;
+    part_ml = ctx->dev_part_ml;
+  }
   rc = enter_stream(ctx, stream);
   if (rc != HEDDLE_OK) return rc;
   StagingSlot* slot = nullptr;
-  rc = acquire_slot(ctx, words, &slot);
+  rc = acquire_slot(ctx, words, &slot, !static_scratch);
   if (rc != HEDDLE_OK) return rc;
   int32_t* w = slot->host;
   DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
@@ -753,9 +789,9 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     kw.head_dim = D;
     kw.one_row_each = 1;
   }
-  rc = upload(ctx, slot, words, stream, args->k_new != nullptr ? &kw : nullptr);
+  rc = upload_to(ctx, slot, words, dev_plan, stream, args->k_new != nullptr ? &kw : nullptr);
   if (rc != HEDDLE_OK) return rc;
-  const int32_t* d = ctx->dev_plan;
+  const int32_t* d = dev_plan;
   ctx->enqueued = true;
 
   const float scale_log2 = ctx->scale * 1.4426950408889634f;
@@ -768,8 +804,8 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     gl.members = d + (h_members - w);
     gl.trajs = d_trajs;
     gl.q = static_cast<const uint16_t*>(args->q);
-    gl.part_acc = ctx->dev_part_acc;
-    gl.part_ml = ctx->dev_part_ml;
+    gl.part_acc = part_acc;
+    gl.part_ml = part_ml;
     gl.n_items = static_cast<int32_t>(n_gitems);
     gl.n_q_heads = Hq;
     gl.n_kv_heads = ctx->cfg.n_kv_heads;
@@ -785,8 +821,8 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
   dl.items = reinterpret_cast<const DecodeItemRec*>(d);
   dl.trajs = d_trajs;
   dl.q = static_cast<const uint16_t*>(args->q);
-  dl.part_acc = ctx->dev_part_acc;
-  dl.part_ml = ctx->dev_part_ml;
+  dl.part_acc = part_acc;
+  dl.part_ml = part_ml;
   dl.out = static_cast<uint16_t*>(args->out);
   dl.lse = args->lse;
   dl.B = B;
@@ -824,6 +860,14 @@ int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, c
     HEDDLE_HIP(launch_decode_combine(dl, stream));
   }
   return HEDDLE_OK;
+}
+
+}  // namespace
+
+int heddle_attn_decode_shared(heddle_ctx* ctx, const heddle_decode_args* args, const int32_t* block_ids_host,
+                              void* hip_stream) {
+  if (block_ids_host == nullptr) return HEDDLE_E_INVAL;
+  return decode_call(ctx, args, block_ids_host, hip_stream, false);
 }
 
 int heddle_plan_append_split(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_host,
@@ -867,181 +911,12 @@ int heddle_plan_append_split(const heddle_ctx* ctx, int32_t B, const int32_t* ct
   return HEDDLE_OK;
 }
 
-namespace {
-
-// The decode step behind heddle_attn_decode (scratch on the heap, grown when a call needs more) and
-// heddle_attn_decode_static (scratch in the library's static device array, nothing allocated).
-int decode_step(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream, bool static_scratch) {
-  {
-    const int rc_args = check_decode_args(ctx, args);
-    if (rc_args != HEDDLE_OK) return rc_args;
-  }
-  const int32_t B = args->B;
-
-  DeviceGuard guard(ctx->cfg.device);
-  if (!guard.ok()) return HEDDLE_E_HIP;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-
-  int32_t chunk = 0;
-  plan_decode(ctx->plan, B, args->len_host, ctx->items, ctx->nsplit, ctx->part_off, chunk);
-  const size_t n_items = ctx->items.size();
-  const size_t n_parts = static_cast<size_t>(ctx->part_off[B]);
-  const int32_t Hq = ctx->cfg.n_q_heads, D = ctx->cfg.head_dim;
-
-  const bool on_matrix_cores = decode_on_matrix_cores(ctx);
-  if (!on_matrix_cores && !decode_shape_supported(Hq / ctx->cfg.n_kv_heads, D)) return HEDDLE_E_UNSUPPORTED;
-
-  // plan image: item records | trajectory records | first_pos[B] | cu_rows[B+1]
-  const size_t words = 8 * n_items + 2 * static_cast<size_t>(B) + 2 * static_cast<size_t>(B) + 1;
-  const size_t acc_elems = n_parts * Hq * D, ml_elems = n_parts * Hq * 4;
-  int32_t* dev_plan = nullptr;
-  float *part_acc = nullptr, *part_ml = nullptr;
-  int rc = HEDDLE_OK;
-  if (static_scratch) {
-    if (ctx->static_scratch == nullptr) {
-      std::snprintf(g_detail, sizeof(g_detail), "hipGetSymbolAddress(scratch) failed when the context was created");
-      return HEDDLE_E_HIP;
-    }
-    const size_t acc_bytes = (acc_elems * sizeof(float) + 255) & ~size_t{255};
-    if (((words + 3) & ~size_t{3}) > kStaticPlanWords || acc_bytes + ml_elems * sizeof(float) > kStaticPartBytes) {
-      std::snprintf(g_detail, sizeof(g_detail),
-                    "static scratch too small: plan image %zu words (limit %zu), partials %zu bytes (limit %zu)",
-                    words, kStaticPlanWords, acc_bytes + ml_elems * sizeof(float), kStaticPartBytes);
-      return HEDDLE_E_NOMEM;
-    }
-    dev_plan = reinterpret_cast<int32_t*>(ctx->static_scratch);
-    part_acc = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t));
-    part_ml = reinterpret_cast<float*>(ctx->static_scratch + kStaticPlanWords * sizeof(int32_t) + acc_bytes);
-  } else {
-    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_acc), &ctx->dev_part_acc_elems, acc_elems, sizeof(float));
-    if (rc != HEDDLE_OK) return rc;
-    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_part_ml), &ctx->dev_part_ml_elems, ml_elems, sizeof(float));
-    if (rc != HEDDLE_OK) return rc;
-    rc = grow_device(reinterpret_cast<void**>(&ctx->dev_plan), &ctx->dev_plan_words, (words + 3) & ~size_t{3},
-                     sizeof(int32_t));
-    if (rc != HEDDLE_OK) return rc;
-    dev_plan = ctx->dev_plan;
-    part_acc = ctx->dev_part_acc;
-    part_ml = ctx->dev_part_ml;
-  }
-  rc = enter_stream(ctx, stream);
-  if (rc != HEDDLE_OK) return rc;
-  StagingSlot* slot = nullptr;
-  rc = acquire_slot(ctx, words, &slot, !static_scratch);
-  if (rc != HEDDLE_OK) return rc;
-  int32_t* w = slot->host;
-  DecodeItemRec* h_items = reinterpret_cast<DecodeItemRec*>(w);
-  DecodeTrajRec* h_trajs = reinterpret_cast<DecodeTrajRec*>(w + 8 * n_items);
-  int32_t* h_first = w + 8 * n_items + 2 * static_cast<size_t>(B);
-  int32_t* h_cu = h_first + B;
-  for (size_t i = 0; i < n_items; ++i) {
-    const DecodeItem& it = ctx->items[i];
-    if (on_matrix_cores) {
-      AppendItemRec& r = reinterpret_cast<AppendItemRec*>(w)[i];
-      r.b = it.b;
-      r.row0 = 0;
-      r.rows_n = 1;
-      r.key_end = std::min(args->len_host[it.b], it.blk_end * HEDDLE_BLOCK_TOKENS);
-      r.step_begin = it.blk_begin / (kAppendStepKeys / HEDDLE_BLOCK_TOKENS);
-      r.slot0 = ctx->part_off[it.b] + it.s;
-      r.nsplit = ctx->nsplit[it.b];
-      r.pad = 0;
-      continue;
-    }
-    DecodeItemRec& r = h_items[i];
-    r.b = it.b;
-    r.slot = ctx->part_off[it.b] + it.s;
-    r.blk_begin = it.blk_begin;
-    r.blk_end = it.blk_end;
-    r.len = args->len_host[it.b];
-    r.table_off = args->row_off_host[it.b];
-    r.nsplit = ctx->nsplit[it.b];
-    r.pad = 0;
-  }
-  for (int32_t b = 0; b < B; ++b) {
-    h_trajs[b].part_off = ctx->part_off[b];
-    h_trajs[b].nsplit = ctx->nsplit[b];
-    h_first[b] = args->len_host[b] - 1;
-    h_cu[b] = b;
-  }
-  h_cu[B] = B;
-  // the step's new K/V rows are stored by the launch that copies the plan image; its row writers
-  // read first_pos from the pinned image
-  KvWriteLaunch kw{};
-  if (args->k_new != nullptr) {
-    kw.pool = static_cast<uint16_t*>(ctx->cfg.kv_pool);
-    kw.row_off = args->row_off;
-    kw.block_ids = args->block_ids;
-    kw.first_pos = static_cast<const int32_t*>(slot->host_dev) + (h_first - w);
-    kw.k = static_cast<const uint16_t*>(args->k_new);
-    kw.v = static_cast<const uint16_t*>(args->v_new);
-    kw.B = B;
-    kw.n_rows = B;
-    kw.n_wblk = B;
-    kw.n_kv_heads = ctx->cfg.n_kv_heads;
-    kw.head_dim = D;
-    kw.one_row_each = 1;
-  }
-  rc = upload_to(ctx, slot, words, dev_plan, stream, args->k_new != nullptr ? &kw : nullptr);
-  if (rc != HEDDLE_OK) return rc;
-  const int32_t* d = dev_plan;
-  ctx->enqueued = true;
-
-  DecodeLaunch dl{};
-  dl.pool = static_cast<const uint16_t*>(ctx->cfg.kv_pool);
-  dl.block_ids = args->block_ids;
-  dl.items = reinterpret_cast<const DecodeItemRec*>(d);
-  dl.trajs = reinterpret_cast<const DecodeTrajRec*>(d + 8 * n_items);
-  dl.q = static_cast<const uint16_t*>(args->q);
-  dl.part_acc = part_acc;
-  dl.part_ml = part_ml;
-  dl.out = static_cast<uint16_t*>(args->out);
-  dl.lse = args->lse;
-  dl.B = B;
-  dl.n_items = static_cast<int32_t>(n_items);
-  dl.n_q_heads = Hq;
-  dl.n_kv_heads = ctx->cfg.n_kv_heads;
-  dl.head_dim = D;
-  dl.scale_log2 = ctx->scale * 1.4426950408889634f;
-  if (on_matrix_cores) {
-    AppendLaunch al{};                         // the step seen as an append: L = len - 1, one new row each
-    al.pool = dl.pool;
-    al.row_off = args->row_off;
-    al.block_ids = args->block_ids;
-    al.ctx_len = d + (h_first - w);
-    al.cu_chunk = d + (h_cu - w);
-    al.items = reinterpret_cast<const AppendItemRec*>(d);
-    al.q = dl.q;
-    al.out = dl.out;
-    al.lse = dl.lse;
-    al.part_acc = dl.part_acc;
-    al.part_ml = dl.part_ml;
-    al.n_items = dl.n_items;
-    al.n_q_heads = Hq;
-    al.n_kv_heads = dl.n_kv_heads;
-    al.head_dim = D;
-    al.scale_log2 = dl.scale_log2;
-    TimedScope t(ctx, 7, stream);
-    HEDDLE_HIP(launch_narrow_attn(al, stream));
-  } else {
-    TimedScope t(ctx, 0, stream);
-    HEDDLE_HIP(launch_decode_splitk(dl, stream));
-  }
-  if (n_parts > static_cast<size_t>(B)) {     // some trajectory was split
-    TimedScope t(ctx, 1, stream);
-    HEDDLE_HIP(launch_decode_combine(dl, stream));
-  }
-  return HEDDLE_OK;
-}
-
-}  // namespace
-
 int heddle_attn_decode(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
-  return decode_step(ctx, args, hip_stream, false);
+  return decode_call(ctx, args, nullptr, hip_stream, false);
 }
 
 int heddle_attn_decode_static(heddle_ctx* ctx, const heddle_decode_args* args, void* hip_stream) {
-  return decode_step(ctx, args, hip_stream, true);
+  return decode_call(ctx, args, nullptr, hip_stream, true);
 }
 
 int heddle_attn_append(heddle_ctx* ctx, const heddle_append_args* args, void* hip_stream) {
