@@ -203,9 +203,10 @@ int heddle_plan_append(const heddle_ctx* ctx, int32_t B, const int32_t* ctx_len_
  *  1. S_t = ceil(extent_t / 64); slots = n_cu * append_wg_per_cu.
  *  2. W = sum S_t, target = max(1, slots / n_kv_heads), chunk = max(ceil(W /
  *     target), append_min_steps); per tile ns = min(ceil(S/chunk), max_split), per =
- *     ceil(S/ns), n = ceil(S/per); if n > 1 and (n-1)*per*64 > L_b + row0 then n -= 1
- *     (the tile's first row must see a key of the last part).  Part k < n-1 covers
- *     steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
+ *     ceil(S/ns), n = ceil(S/per); while n > 1 and (n-1)*per*64 > L_b + row0: n -= 1
+ *     (the tile's first row must see a key of the last part: no row of a part is an
+ *     empty softmax).  Part k < n-1 covers steps [k*per, (k+1)*per), the last part
+ *     [(n-1)*per, S).
  *  3. a tile with n > 1 owns rows_n * n partial slots from part_base_t (assigned in
  *     tile order); row r, part k -> part_base_t + r*n + k.
  *  4. items (t, k) sorted by (-(step_end - step_begin), b_t, step_begin, row0_t): equally

@@ -243,9 +243,10 @@ def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_
       1. S_t = ceil(extent_t / 64) steps; slots = n_cu * append_wg_per_cu.
       2. W = sum S_t, target = max(1, slots // n_kv_heads),
          chunk = max(ceil(W / target), min_steps).  Per tile ns = min(ceil(S/chunk), max_split),
-         per = ceil(S / ns), n = ceil(S / per); if n > 1 and (n-1) * per * 64 > L_b + row0 then
-         n -= 1 (the first row of the tile must see a key of the last part).  Part k < n-1
-         covers steps [k*per, (k+1)*per), the last part [(n-1)*per, S).
+         per = ceil(S / ns), n = ceil(S / per); while n > 1 and (n-1) * per * 64 > L_b + row0:
+         n -= 1 (the first row of the tile must see a key of the last part, or that row's share
+         of the part would be an empty softmax).  Part k < n-1 covers steps [k*per, (k+1)*per),
+         the last part [(n-1)*per, S).
       3. Tiles with n > 1 own rows_n * n partial slots from part_base_t on (bases assigned in
          tile order); row r of the tile, part k -> slot part_base_t + r*n + k.
       4. items (t, k) sorted by (-(step_end - step_begin), b_t, step_begin, row0_t): among equally
@@ -265,7 +266,7 @@ def split_append_tiles(plan, ctx_lens, n_kv_heads: int, n_cu=256, append_wg_per_
         per = _ceil_div(S[t], ns)
         n = _ceil_div(S[t], per)
         first_row_pos = int(ctx_lens[int(plan["tile_b"][t])]) + int(plan["tile_row0"][t])
-        if n > 1 and (n - 1) * per * APPEND_STEP_KEYS > first_row_pos:
+        while n > 1 and (n - 1) * per * APPEND_STEP_KEYS > first_row_pos:
             n -= 1
         nsplit[t], per_of[t] = n, per
     base, part_base, items = 0, [], []

@@ -207,9 +207,10 @@ void split_append_tiles(const PlanParams& p, int32_t append_wg_per_cu, int32_t m
     const int64_t want = std::min<int64_t>(ceil_div(steps[t], chunk), p.max_split);
     const int64_t each = ceil_div(steps[t], want);
     int64_t parts = ceil_div(steps[t], each);
-    // the first row of the tile must see a key of the last part
+    // the first row of the tile must see a key of the last part (with parts of one or two steps
+    // more than one part may lie behind what that row sees)
     const int64_t first_row_pos = static_cast<int64_t>(ctx_len[tiles[t].b]) + tiles[t].row0;
-    if (parts > 1 && (parts - 1) * each * kAppendStepKeys > first_row_pos) --parts;
+    while (parts > 1 && (parts - 1) * each * kAppendStepKeys > first_row_pos) --parts;
     out.nsplit[t] = static_cast<int32_t>(parts);
     per[t] = each;
   }

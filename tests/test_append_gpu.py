@@ -325,6 +325,25 @@ def test_straggler_append_workload_at_full_size_every_row():
     assert np.array_equal(dc.pool_bits(), pool)
 
 
+@pytest.mark.parametrize("n_q,n_kv,d", [(2, 2, 64), (2, 2, 128), (1, 1, 128)])
+def test_tall_tiles_over_short_contexts_with_one_step_parts(n_q, n_kv, d):
+    """One query head per kv head makes tiles of 128 chunk rows; with parts of a single 64-key step
+    (append_min_steps = 1 on a large grid) several candidate parts of such a tile can lie behind
+    what its first row sees.  They are all merged back (a row with an empty share of a part would
+    be an empty softmax), and the result stays the oracle's."""
+    c = small(41, [31, 7, 70, 0, 130, 64], [106, 75, 106, 128, 200, 127], n_q, n_kv, d)
+    kw = dict(n_cu=256, append_wg_per_cu=4, append_min_steps=1)
+    dc = DeviceCase(c, **kw)
+    sp = dc.ctx.plan_append_split(c["lens"], c["cu_chunk"])
+    first_tile = {int(b): int(n) for b, r0, n in zip(sp["tile_b"], sp["tile_row0"], sp["tile_nsplit"]) if r0 == 0}
+    assert first_tile == {0: 1, 1: 1, 2: 2, 3: 1, 4: 3, 5: 2}
+    pool, ref, ref_lse, spread = oracle_append(c)
+    out, lse = dc.append()
+    assert_close(out, ref, "tall tiles, one-step parts", spread)
+    assert_lse_close(lse, ref_lse, "tall tiles, one-step parts lse")
+    assert np.array_equal(dc.pool_bits(), pool)
+
+
 def test_append_up_to_the_maximum_context():
     """Chunks that end exactly at the largest context the library accepts, one through the
     128-row kernel (40 rows), one through the short-row kernel (3 rows), both cut into parts."""

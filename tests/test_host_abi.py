@@ -358,15 +358,15 @@ def test_placement_errors():
 
 def test_append_split_matches_oracle():
     rng = np.random.default_rng(31)
-    for trial in range(80):
+    for trial in range(300):
         B = int(rng.integers(1, 6))
-        L = rng.integers(0, 20000, B).astype(np.int32)
-        Cn = rng.integers(1, 70, B)
+        L = rng.integers(0, int(rng.choice([40, 300, 20000])), B).astype(np.int32)   # short contexts under tall tiles too
+        Cn = rng.integers(1, int(rng.choice([70, 400])), B)
         cu = np.concatenate([[0], np.cumsum(Cn)]).astype(np.int32)
         G = int(rng.choice([1, 4, 8]))
         n_kv = int(rng.choice([1, 2, 8]))
-        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 3)),
-                   append_min_steps=int(rng.choice([1, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
+        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 5)),
+                   append_min_steps=int(rng.choice([1, 2, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
         c = heddle.Context(n_kv * G, n_kv, 128, 4, **prm)
         got = c.plan_append_split(L, cu)
         plan = op.plan_append(L, Cn, 128 // G)

@@ -381,18 +381,31 @@ def test_append_split_hand_example():
     sp = op.split_append_tiles(plan, [60], 1, n_cu=64, append_wg_per_cu=2, min_steps=1, max_split=8)
     by_row0 = {int(r): int(n) for r, n in zip(plan["tile_row0"], sp["tile_nsplit"])}
     assert by_row0 == {0: 1, 32: 2, 64: 2, 96: 3}
+    # L = 31, C = 106 in one tile of 128 rows: extent 137 -> S = 3 steps.  n_kv = 2, 256 CUs x 4: target 512,
+    # chunk = max(ceil(3/512), 1) = 1; ns = 3, per = 1, n = 3.  The first row sees keys 0..31 only: the third
+    # part would start at key 128, the second at key 64, both behind it -> n = 3 -> 2 -> 1, the tile stays whole.
+    plan = op.plan_append([31], [106], 128)
+    sp = op.split_append_tiles(plan, [31], 2, n_cu=256, append_wg_per_cu=4, min_steps=1)
+    assert sp["tile_nsplit"].tolist() == [1] and sp["n_slots"] == 0
+    assert sp["item_step_begin"].tolist() == [0] and sp["item_step_end"].tolist() == [3]
+    # the same tile behind L = 70: the first row sees keys 0..70, the second part (from key 64) stays, the
+    # third (from key 128) is merged into it
+    plan = op.plan_append([70], [106], 128)
+    sp = op.split_append_tiles(plan, [70], 2, n_cu=256, append_wg_per_cu=4, min_steps=1)
+    assert sp["tile_nsplit"].tolist() == [2] and sp["n_slots"] == 2 * 106
+    assert sorted(zip(sp["item_step_begin"].tolist(), sp["item_step_end"].tolist())) == [(0, 1), (1, 3)]
 
 
 def test_append_split_invariants():
     rng = np.random.default_rng(21)
-    for trial in range(80):
+    for trial in range(400):
         B = int(rng.integers(1, 6))
-        L = rng.integers(0, 20000, B)
-        C = rng.integers(1, 70, B)
+        L = rng.integers(0, int(rng.choice([40, 300, 20000])), B)      # short contexts under tall tiles included
+        C = rng.integers(1, int(rng.choice([70, 400])), B)
         R = int(rng.choice([16, 32, 128]))
         n_kv = int(rng.choice([1, 2, 8]))
-        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 3)),
-                   min_steps=int(rng.choice([1, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
+        prm = dict(n_cu=int(rng.choice([4, 64, 256])), append_wg_per_cu=int(rng.integers(1, 5)),
+                   min_steps=int(rng.choice([1, 2, 4, 8])), max_split=int(rng.choice([2, 16, 64])))
         plan = op.plan_append(L, C, R)
         sp = op.split_append_tiles(plan, L, n_kv, **prm)
         used = np.zeros(sp["n_slots"], dtype=np.int32)
