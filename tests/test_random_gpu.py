@@ -14,7 +14,13 @@ from tests.gpu_util import (DeviceCase, assert_close, assert_lse_close, bf16_to_
 pytestmark = pytest.mark.gpu
 
 # more seeds per test for an occasional longer run: HEDDLE_RANDOM_CASES=100 python -m pytest tests/test_random_gpu.py
+# (HEDDLE_RANDOM_FIRST=1000 starts them at seed 1000)
 EXTRA = int(os.environ.get("HEDDLE_RANDOM_CASES", "0"))
+FIRST = int(os.environ.get("HEDDLE_RANDOM_FIRST", "0"))
+
+
+def seeds(default):
+    return range(FIRST, FIRST + max(default, EXTRA))
 
 HEAD_SHAPES = [(1, 1, 128), (2, 2, 64), (2, 1, 128), (4, 1, 128), (8, 2, 128), (8, 1, 128), (16, 2, 128),
                (16, 4, 64), (32, 8, 128), (8, 8, 64), (6, 3, 128), (10, 2, 128), (40, 8, 128), (6, 2, 128),
@@ -43,7 +49,7 @@ def draw_plan_kw(rng):
                 max_split=int(rng.choice([1, 2, 5, 64])))
 
 
-@pytest.mark.parametrize("seed", range(max(12, EXTRA)))
+@pytest.mark.parametrize("seed", seeds(12))
 def test_random_decode(seed):
     rng = np.random.default_rng([101, seed])
     n_q, n_kv, d = HEAD_SHAPES[int(rng.integers(0, len(HEAD_SHAPES)))]
@@ -78,7 +84,7 @@ def test_random_decode(seed):
         assert np.array_equal(dc.pool_bits(), pool), "pool after the new rows differs from the oracle's"
 
 
-@pytest.mark.parametrize("seed", range(max(10, EXTRA)))
+@pytest.mark.parametrize("seed", seeds(10))
 def test_random_append(seed):
     rng = np.random.default_rng([102, seed])
     shapes = [s for s in HEAD_SHAPES if s[2] == 128 or s[0] // s[1] in POW2]
@@ -106,7 +112,7 @@ def test_random_append(seed):
     assert_lse_close(lse, ref_lse, f"random append lse {seed}")
 
 
-@pytest.mark.parametrize("seed", range(max(8, EXTRA)))
+@pytest.mark.parametrize("seed", seeds(8))
 def test_random_shared_decode(seed):
     rng = np.random.default_rng([103, seed])
     n_q, n_kv, d = [(8, 2, 128), (4, 1, 128), (16, 2, 128), (32, 8, 128), (2, 2, 128), (10, 2, 128), (40, 8, 128),
