@@ -325,6 +325,26 @@ def test_straggler_append_workload_at_full_size_every_row():
     assert np.array_equal(dc.pool_bits(), pool)
 
 
+@pytest.mark.parametrize("n_q,n_kv,d", [(2, 2, 128), (8, 2, 128), (10, 2, 128), (16, 2, 128), (2, 2, 64), (8, 2, 64)])
+def test_tiles_of_at_most_64_rows(n_q, n_kv, d):
+    """Tiles whose rows (chunk rows x query heads per kv head) number 64, one chunk row more, one
+    chunk row less and a single row: half of the workgroup's row slots or fewer carry a row.  Over
+    contexts in which the second half of the first 64-key step lies wholly, partly or not at all
+    behind what the rows see, and over contexts long enough to be cut into parts."""
+    G = n_q // n_kv
+    h = 64 // G
+    L = [0, 5, 31, 32, 33, 63, 64, 100, 1000, 3000, 0, 40]
+    C = [h, h, 1, h, max(1, h - 1), h, h + 1, h, h, h, h + 1, 128 // G + h]
+    c = small(42, L, C, n_q, n_kv, d)
+    pool, ref, ref_lse, spread = oracle_append(c)
+    for kw in ({}, dict(n_cu=64, append_wg_per_cu=4, append_min_steps=1)):
+        dc = DeviceCase(c, **kw)
+        out, lse = dc.append()
+        assert_close(out, ref, f"tiles of at most 64 rows {kw}", spread)
+        assert_lse_close(lse, ref_lse, f"tiles of at most 64 rows lse {kw}")
+        assert np.array_equal(dc.pool_bits(), pool)
+
+
 @pytest.mark.parametrize("n_q,n_kv,d", [(2, 2, 64), (2, 2, 128), (1, 1, 128)])
 def test_tall_tiles_over_short_contexts_with_one_step_parts(n_q, n_kv, d):
     """One query head per kv head makes tiles of 128 chunk rows; with parts of a single 64-key step
