@@ -99,6 +99,8 @@ def test_random_append(seed):
     kw = {} if rng.integers(0, 2) else dict(n_cu=int(rng.choice([2, 16, 256])),
                                             append_wg_per_cu=int(rng.choice([1, 2, 4])),
                                             append_min_steps=int(rng.choice([1, 2, 4, 8])))
+    if kw and rng.integers(0, 2):
+        kw["max_split"] = int(rng.choice([1, 2, 5, 64]))
     print(f"random append seed {seed}: heads {n_q}/{n_kv} B {B} L {L.tolist()} C {C.tolist()} ctx {kw}", flush=True)
     c = hw.build_case(entropy=[102, seed], lens=L, chunk_lens=C, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=d,
                       threads=4)
@@ -133,6 +135,13 @@ def test_random_shared_decode(seed):
     group_of, lens = np.asarray(group_of)[order], np.asarray(lens, dtype=np.int32)[order]
     kw = {} if rng.integers(0, 2) else dict(min_share_blk=int(rng.choice([1, 4, 16])),
                                             group_wg_per_cu=int(rng.choice([1, 2])), n_cu=int(rng.choice([4, 64, 256])))
+    if kw and rng.integers(0, 2):
+        kw.update(wg_per_cu=int(rng.choice([1, 2, 4, 8])), min_chunk_blk=int(rng.choice([1, 4, 16, 32])),
+                  max_split=int(rng.choice([1, 2, 5, 64])))
+        if n_q // n_kv in (1, 2, 4) or d == 64:
+            kw["tile_blk"] = int(rng.choice([1, 4, 8]))       # the matrix-core kernel needs multiples of 4
+        else:
+            kw["tile_blk"] = int(rng.choice([4, 8]))
     print(f"random shared decode seed {seed}: heads {n_q}/{n_kv} groups {shared} members "
           f"{np.bincount(group_of[group_of >= 0]).tolist()} B {len(lens)} ctx {kw}", flush=True)
     c = hw.build_case(entropy=[103, seed], lens=lens, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=d,
