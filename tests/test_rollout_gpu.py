@@ -7,7 +7,11 @@ preempted trajectory keeps its cache; Sec. 7: the samples of a prompt share its 
   another, later it is unpacked under new blocks -> decode with shared prompt blocks.
 
 The library's block manager hands out the blocks; the float64 oracle mirrors every call on its own
-copy of the pool, and outputs and the pool are compared after each call.  Needs the GPU."""
+copy of the pool, and outputs and the pool are compared after each call.  A second test draws
+such rollouts at random: head shape, prompts and samples, and a sequence of decode steps, tool
+outputs, preemptions, resumptions, departures and arrivals.  Needs the GPU."""
+import os
+
 import numpy as np
 import pytest
 
@@ -30,15 +34,16 @@ def bf16(rng, shape):
 class Worker:
     """Library context and oracle state side by side."""
 
-    def __init__(self, seed):
+    def __init__(self, seed, n_q=N_Q, n_kv=N_KV, d=D, n_blocks=N_BLOCKS):
         import paper_2603_28101_amd as heddle
         torch = torch_mod()
         self.rng = np.random.default_rng(seed)
-        pool = np.full((N_BLOCKS, N_KV, 2, 16 * D), 0x7FC0, dtype=np.uint16)       # everything starts as NaN
+        self.n_q, self.n_kv, self.d = n_q, n_kv, d
+        pool = np.full((n_blocks, n_kv, 2, 16 * d), 0x7FC0, dtype=np.uint16)       # everything starts as NaN
         self.ref_pool = pool.copy()
         self.pool = to_dev_bf16(pool)
-        self.ctx = heddle.Context(N_Q, N_KV, D, N_BLOCKS, kv_pool=self.pool, device=0)
-        self.ref_blocks = KVManager(N_BLOCKS)
+        self.ctx = heddle.Context(n_q, n_kv, d, n_blocks, kv_pool=self.pool, device=0)
+        self.ref_blocks = KVManager(n_blocks)
         self.tables = []          # per trajectory: list of physical blocks
         self.lens = []            # tokens stored
         self.torch = torch
@@ -68,15 +73,16 @@ class Worker:
             self.grow(b, self.lens[b] + c)
         row_off, ids = self.csr(order)
         n_rows = int(sum(chunk_lens))
-        q, k, v = bf16(rng, (n_rows, N_Q, D)), bf16(rng, (n_rows, N_KV, D)), bf16(rng, (n_rows, N_KV, D))
+        q = bf16(rng, (n_rows, self.n_q, self.d))
+        k, v = bf16(rng, (n_rows, self.n_kv, self.d)), bf16(rng, (n_rows, self.n_kv, self.d))
         L = np.asarray([self.lens[b] for b in order], dtype=np.int32)
         cu = np.concatenate([[0], np.cumsum(chunk_lens)]).astype(np.int32)
-        out = torch.full((n_rows, N_Q, D), float("nan"), dtype=torch.bfloat16, device="cuda")
-        lse = torch.full((n_rows, N_Q), float("nan"), dtype=torch.float32, device="cuda")
+        out = torch.full((n_rows, self.n_q, self.d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((n_rows, self.n_q), float("nan"), dtype=torch.float32, device="cuda")
         self.ctx.attn_append(L, cu, row_off, to_dev_i32(row_off), to_dev_i32(ids), to_dev_bf16(q), to_dev_bf16(k),
                              to_dev_bf16(v), out, lse)
         torch.cuda.synchronize()
-        ref, ref_lse, spread = oa.append(self.ref_pool, row_off, ids, L, cu, q, k, v, N_KV, with_spread=True,
+        ref, ref_lse, spread = oa.append(self.ref_pool, row_off, ids, L, cu, q, k, v, self.n_kv, with_spread=True,
                                          centered=None)
         assert_close(bits_to_f64(bf16_to_host_bits(out)), ref, what, spread)
         assert_lse_close(lse.cpu().numpy(), ref_lse, what)
@@ -84,33 +90,87 @@ class Worker:
             self.lens[b] += c
         self.check_pool(what)
 
-    def decode(self, order, what, shared=False):
+    def decode(self, order, what, shared=False, expect_groups=True):
         rng, torch = self.rng, self.torch
         for b in order:
             self.grow(b, self.lens[b] + 1)
         row_off, ids = self.csr(order)
         B = len(order)
-        q, k, v = bf16(rng, (B, N_Q, D)), bf16(rng, (B, N_KV, D)), bf16(rng, (B, N_KV, D))
+        q = bf16(rng, (B, self.n_q, self.d))
+        k, v = bf16(rng, (B, self.n_kv, self.d)), bf16(rng, (B, self.n_kv, self.d))
         lens = np.asarray([self.lens[b] + 1 for b in order], dtype=np.int32)      # the new row included
-        out = torch.full((B, N_Q, D), float("nan"), dtype=torch.bfloat16, device="cuda")
-        lse = torch.full((B, N_Q), float("nan"), dtype=torch.float32, device="cuda")
+        out = torch.full((B, self.n_q, self.d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, self.n_q), float("nan"), dtype=torch.float32, device="cuda")
         args = (to_dev_i32(row_off), to_dev_i32(ids), to_dev_bf16(q), out, lse, to_dev_bf16(k), to_dev_bf16(v))
         if shared:
             plan = self.ctx.plan_decode_shared(lens, row_off, ids)
-            assert plan["n_groups"] >= 1, "the samples of a prompt were expected to share its blocks"
+            assert plan["n_groups"] >= 1 or not expect_groups, "the samples of a prompt were expected to share its blocks"
             self.ctx.attn_decode_shared(lens, row_off, ids, *args)
         else:
             self.ctx.attn_decode(lens, row_off, *args)
         torch.cuda.synchronize()
         for i in range(B):
             oa.write_kv(self.ref_pool, row_off, ids, [int(lens[i]) - 1], i, k[i:i + 1], v[i:i + 1])
-        ref, ref_lse, spread = oa.decode(self.ref_pool, row_off, ids, lens, q, N_KV, with_spread=True,
+        ref, ref_lse, spread = oa.decode(self.ref_pool, row_off, ids, lens, q, self.n_kv, with_spread=True,
                                          centered=None if shared else True)
         assert_close(bits_to_f64(bf16_to_host_bits(out)), ref, what, spread)
         assert_lse_close(lse.cpu().numpy(), ref_lse, what)
         for b in order:
             self.lens[b] += 1
         self.check_pool(what)
+
+
+    def fork(self, leader, members):
+        """The members start from the leader's whole blocks (one more holder each) and from a copy of
+        its partly filled last block in a block of their own."""
+        whole = self.lens[leader] // 16
+        for b in members:
+            self.tables[b] = list(self.tables[leader][:whole])
+            if whole:
+                self.ctx.kv_retain(np.asarray(self.tables[b], dtype=np.int32))
+                assert self.ref_blocks.retain(self.tables[b]) == 0
+            self.lens[b] = whole * 16
+            self.grow(b, self.lens[leader])
+            self.lens[b] = self.lens[leader]
+        if self.lens[leader] % 16 and members:
+            src = [self.tables[leader][whole]] * len(members)
+            dst = [self.tables[b][whole] for b in members]
+            self.ctx.kv_copy(np.asarray(src, dtype=np.int32), np.asarray(dst, dtype=np.int32))
+            oa.copy_blocks(self.ref_pool, src, dst)
+            self.torch.cuda.synchronize()
+        self.check_pool("fork")
+
+    def release(self, b):
+        self.ctx.kv_free(np.asarray(self.tables[b], dtype=np.int32))
+        assert self.ref_blocks.free(self.tables[b]) == 0
+        assert self.ctx.kv_num_free() == self.ref_blocks.num_free()
+        self.tables[b] = []
+
+    def preempt(self, b):
+        """Packs the trajectory's whole cache (shared blocks included) and frees its table."""
+        torch = self.torch
+        n_blk = -(-self.lens[b] // 16)
+        blocks = self.tables[b][:n_blk]
+        staging = torch.empty((n_blk, self.n_kv * 2 * 16 * self.d), dtype=torch.bfloat16, device="cuda")
+        self.ctx.kv_pack(np.asarray(blocks, dtype=np.int32), staging)
+        torch.cuda.synchronize()
+        row_off, ids = self.csr([b])
+        staged_ref = oa.pack(self.ref_pool, row_off, ids, 0, self.lens[b])
+        assert np.array_equal(bf16_to_host_bits(staging).reshape(staged_ref.shape), staged_ref)
+        self.release(b)
+        return staging, staged_ref
+
+    def resume(self, b, staging, staged_ref):
+        """The trajectory comes back under whatever blocks are free now (all its own from here on)."""
+        n_blk = staged_ref.shape[0]
+        got = self.ctx.kv_alloc(n_blk)
+        code, ref_ids = self.ref_blocks.alloc(n_blk)
+        assert code == 0 and got.tolist() == ref_ids
+        self.ctx.kv_unpack(got, staging)
+        self.torch.cuda.synchronize()
+        oa.unpack(self.ref_pool, got, staged_ref)
+        self.tables[b] = got.tolist()
+        self.check_pool("unpack")
 
 
 def test_rollout_of_six_trajectories():
@@ -192,3 +252,84 @@ def test_rollout_of_six_trajectories():
         w.ctx.kv_free(np.asarray(w.tables[b], dtype=np.int32))
         assert w.ref_blocks.free(w.tables[b]) == 0
     assert w.ctx.kv_num_free() == N_BLOCKS == w.ref_blocks.num_free()
+
+
+SEEDS = range(int(os.environ.get("HEDDLE_RANDOM_FIRST", "0")),
+              int(os.environ.get("HEDDLE_RANDOM_FIRST", "0")) + max(6, int(os.environ.get("HEDDLE_RANDOM_CASES", "0"))))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_rollout(seed):
+    """A rollout drawn at random: a head shape, one to three prompts with one to four samples each,
+    then a dozen steps, each a decode step (plain or shared-prefix) of a random subset in random
+    order, tool outputs of random sizes, a preemption (pack, free), a resumption (alloc, unpack), a
+    departure (free) or an arrival (a new prompt into recycled blocks).  The oracle mirrors every
+    call; outputs, block ids and the whole pool are compared after each."""
+    rng = np.random.default_rng([104, seed])
+    n_q, n_kv, d = [(8, 2, 128), (4, 1, 128), (16, 2, 128), (2, 2, 128), (10, 2, 128), (8, 2, 64), (32, 8, 128)][
+        int(rng.integers(0, 7))]
+    n_blocks = 700
+    w = Worker([104, seed, 1], n_q, n_kv, d, n_blocks)
+    n_prompts = int(rng.integers(1, 4))
+    groups = [int(rng.integers(1, 5)) for _ in range(n_prompts)]
+    n_traj = sum(groups)
+    w.tables = [[] for _ in range(n_traj)]
+    w.lens = [0] * n_traj
+    leaders, b = [], 0
+    for g in groups:
+        leaders.append(b)
+        b += g
+    prompt_len = [int(rng.choice([5, 16, 40, 75, 128, 200, 333])) for _ in range(n_prompts)]
+    print(f"random rollout {seed}: heads {n_q}/{n_kv} d {d} prompts {prompt_len} samples {groups}", flush=True)
+    w.append(leaders, prompt_len, "prompt prefill")
+    for leader, g in zip(leaders, groups):
+        w.fork(leader, list(range(leader + 1, leader + g)))
+    live, away = set(range(n_traj)), {}
+    for step in range(12):
+        op = str(rng.choice(["decode", "decode", "shared", "shared", "append", "append", "preempt", "resume", "leave",
+                             "arrive"]))
+        room = w.ctx.kv_num_free()
+        members = sorted(live)
+        what = f"rollout {seed} step {step} {op}"
+        if op in ("decode", "shared") and members:
+            order = [int(x) for x in rng.permutation(members)[:int(rng.integers(1, len(members) + 1))]]
+            if room < len(order):
+                continue
+            print(what, order, flush=True)
+            w.decode(order, what, shared=op == "shared", expect_groups=False)
+        elif op == "append" and members:
+            order = [int(x) for x in rng.permutation(members)[:int(rng.integers(1, len(members) + 1))]]
+            chunk = [int(rng.choice([1, 3, 8, 17, 40, 90, 160])) for _ in order]
+            if room < sum(-(-c // 16) + 1 for c in chunk):
+                continue
+            print(what, order, chunk, flush=True)
+            w.append(order, chunk, what)
+        elif op == "preempt" and len(members) > 1:
+            b = int(rng.choice(members))
+            print(what, b, flush=True)
+            away[b] = w.preempt(b)
+            live.discard(b)
+        elif op == "resume" and away:
+            b = int(rng.choice(sorted(away)))
+            if room < away[b][1].shape[0]:
+                continue
+            print(what, b, flush=True)
+            w.resume(b, *away.pop(b))
+            live.add(b)
+        elif op == "leave" and len(members) > 1:
+            b = int(rng.choice(members))
+            print(what, b, flush=True)
+            w.release(b)
+            live.discard(b)
+        elif op == "arrive" and room > 40:
+            w.tables.append([])
+            w.lens.append(0)
+            b = len(w.lens) - 1
+            n = int(rng.choice([1, 16, 50, 129, 300]))
+            print(what, b, n, flush=True)
+            w.append([b], [n], what)
+            live.add(b)
+    for b in sorted(live):
+        w.release(b)
+    # trajectories still away hold no blocks: everything is free again
+    assert w.ctx.kv_num_free() == n_blocks == w.ref_blocks.num_free()
