@@ -107,6 +107,39 @@ def test_calls_of_one_context_on_two_streams_are_ordered():
     assert np.array_equal(bf16_to_host_bits(staging).reshape(packed.shape), packed)
 
 
+def test_two_contexts_over_one_pool_overlap_on_two_streams():
+    """The documented way to stage a cache while decode runs: a second context over the same pool
+    on a second stream.  Nothing orders the two contexts against each other (each has its own plan
+    buffer and staging ring), both only read the pool: eight decode steps on one stream interleaved
+    with eight packs on the other, no synchronisation in between, every result as if issued alone."""
+    torch = torch_mod()
+    lens = np.array([9000, 300, 4100, 2500, 12000, 640], dtype=np.int32)
+    case = hw.build_case(entropy=[0x57, 4], lens=lens, n_q_heads=8, n_kv_heads=2, head_dim=128, threads=4)
+    dc = DeviceCase(case)
+    side = heddle.Context(8, 2, 128, case["n_blocks"], kv_pool=dc.pool, device=0)
+    dc.ctx.reserve(len(lens))
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.full_like(dc.out, float("nan")) for _ in range(8)]
+    stagings, packed_ref = [], []
+    for i in range(8):
+        t = i % len(lens)
+        ids = case["block_ids"][case["row_off"][t]:case["row_off"][t + 1]]
+        stagings.append((ids, torch.zeros((len(ids), 2 * 2 * 16 * 128), dtype=torch.bfloat16, device="cuda")))
+        packed_ref.append(oa.pack(case["pool"], case["row_off"], case["block_ids"], t, int(lens[t])))
+    step_lens = [np.maximum(1, lens - 37 * i).astype(np.int32) for i in range(8)]
+    torch.cuda.synchronize()
+    for i in range(8):
+        dc.ctx.attn_decode(step_lens[i], case["row_off"], dc.row_off, dc.block_ids, dc.q, outs[i], None, stream=a)
+        side.kv_pack(stagings[i][0], stagings[i][1], stream=b)
+    torch.cuda.synchronize()
+    for i in range(8):
+        ref, _, spread = oa.decode(case["pool"], case["row_off"], case["block_ids"], step_lens[i], case["q"], 2,
+                                   with_spread=True)
+        assert_close(bits_to_f64(bf16_to_host_bits(outs[i])), ref, f"decode {i} beside a pack", spread)
+        got = bf16_to_host_bits(stagings[i][1]).reshape(packed_ref[i].shape)
+        assert np.array_equal(got, packed_ref[i]), f"pack {i} beside a decode"
+
+
 def test_misaligned_pointers_are_refused():
     torch = torch_mod()
     case = hw.build_case(entropy=[0x57, 4], lens=[50, 9], n_q_heads=8, n_kv_heads=2, head_dim=128, threads=1)
