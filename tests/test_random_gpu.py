@@ -114,6 +114,33 @@ def test_random_append(seed):
     assert_lse_close(lse, ref_lse, f"random append lse {seed}")
 
 
+@pytest.mark.parametrize("seed", seeds(3))
+def test_random_append_tall(seed):
+    """Chunks of a few hundred rows (many row tiles per trajectory, each cut over its keys when
+    the planner's parameters say so) behind contexts from empty to a few thousand tokens."""
+    rng = np.random.default_rng([105, seed])
+    shapes = [s for s in HEAD_SHAPES if s[2] == 128 or s[0] // s[1] in POW2]
+    n_q, n_kv, d = shapes[int(rng.integers(0, len(shapes)))]
+    B = int(rng.integers(1, 3))
+    L = rng.integers(0, int(rng.choice([70, 600, 2000])), B).astype(np.int32)
+    C = rng.integers(130, 400, B).astype(np.int32)
+    kw = {} if rng.integers(0, 3) == 0 else dict(n_cu=int(rng.choice([16, 256])),
+                                                 append_wg_per_cu=int(rng.choice([1, 2, 4])),
+                                                 append_min_steps=int(rng.choice([1, 2, 4])),
+                                                 max_split=int(rng.choice([2, 5, 64])))
+    print(f"random tall append seed {seed}: heads {n_q}/{n_kv} d {d} L {L.tolist()} C {C.tolist()} ctx {kw}", flush=True)
+    c = hw.build_case(entropy=[105, seed], lens=L, chunk_lens=C, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=d,
+                      threads=4)
+    dc = DeviceCase(c, **kw)
+    out, lse = dc.append()
+    pool = c["pool"].copy()
+    ref, ref_lse, spread = oa.append(pool, c["row_off"], c["block_ids"], c["lens"], c["cu_chunk"], c["q"], c["k_new"],
+                                     c["v_new"], n_kv, with_spread=True, centered=None)
+    assert np.array_equal(dc.pool_bits(), pool), "pool after append differs from the oracle's"
+    assert_close(out, ref, f"random tall append {seed}", spread)
+    assert_lse_close(lse, ref_lse, f"random tall append lse {seed}")
+
+
 @pytest.mark.parametrize("seed", seeds(8))
 def test_random_shared_decode(seed):
     rng = np.random.default_rng([103, seed])
