@@ -490,17 +490,36 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeLaunch a) {
   const int j = blockIdx.x - b * a.n_q_heads;
   const int e = threadIdx.x;
   const int p0 = tr.part_off;
-  float M = -INFINITY;
-#pragma unroll 8
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(p0 + s) * a.n_q_heads + j) * 4]);
-  float num = 0.0f, den = 0.0f, den_exact = 0.0f;
-#pragma unroll 8
-  for (int s = 0; s < ns; ++s) {   // unrolled so that the loads of several parts are in flight together
-    const int64_t pj = static_cast<int64_t>(p0 + s) * a.n_q_heads + j;
-    const float f = __builtin_amdgcn_exp2f(a.part_ml[pj * 4] - M);
-    den = fmaf(f, a.part_ml[pj * 4 + 1], den);
-    den_exact = fmaf(f, a.part_ml[pj * 4 + 2], den_exact);
-    num = fmaf(f, a.part_acc[pj * D + e], num);
+  // Parts are taken eight at a time, all loads of a round issued together (a part index past the
+  // last one repeats the last part with weight 0), and merged into the running state with the
+  // reference maximum moved as in the kernels; up to eight parts this is the plain two-pass form.
+  float M = -INFINITY, num = 0.0f, den = 0.0f, den_exact = 0.0f;
+  for (int s0 = 0; s0 < ns; s0 += 8) {
+    float m[8], l[8], lx[8], ac[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t pj = static_cast<int64_t>(p0 + min(s0 + i, ns - 1)) * a.n_q_heads + j;
+      const float4 ml = *reinterpret_cast<const float4*>(a.part_ml + pj * 4);
+      m[i] = s0 + i < ns ? ml.x : -INFINITY;
+      l[i] = ml.y;
+      lx[i] = ml.z;
+      ac[i] = a.part_acc[pj * D + e];
+    }
+    float m_new = M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m_new = fmaxf(m_new, m[i]);
+    const float keep = __builtin_amdgcn_exp2f(M - m_new);     // 0 in the first round (nothing kept yet)
+    num *= keep;
+    den *= keep;
+    den_exact *= keep;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float f = __builtin_amdgcn_exp2f(m[i] - m_new);
+      den = fmaf(f, l[i], den);
+      den_exact = fmaf(f, lx[i], den_exact);
+      num = fmaf(f, ac[i], num);
+    }
+    M = m_new;
   }
   const int64_t oj = static_cast<int64_t>(a.out_row != nullptr ? a.out_row[b] : b) * a.n_q_heads + j;
   a.out[oj * D + e] = f32_to_bf16_rne(num / den);
