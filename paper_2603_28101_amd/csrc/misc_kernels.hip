@@ -21,24 +21,15 @@ __device__ __forceinline__ void kv_write_block(const KvWriteLaunch& a, int wg) {
   __shared__ __attribute__((aligned(16))) uint16_t s_v[16][kMaxD + 8];
   const int wb = wg / a.n_kv_heads;
   const int h = wg - wb * a.n_kv_heads;
-  int b, n_new, blk_in_traj;
-  int64_t row0;
-  if (a.one_row_each) {                       // a decode step: write block wb is trajectory wb's
-    b = wb;
-    n_new = 1;
-    blk_in_traj = 0;
-    row0 = b;
-  } else {
-    int lo = 0, hi = a.B;                     // trajectory of this write block: last b with cu_wblk[b] <= wb
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (a.cu_wblk[mid] <= wb) lo = mid; else hi = mid;
-    }
-    b = lo;
-    n_new = a.cu_rows[b + 1] - a.cu_rows[b];
-    blk_in_traj = wb - a.cu_wblk[b];
-    row0 = a.cu_rows[b];
+  int lo = 0, hi = a.B;                       // trajectory of this write block: last b with cu_wblk[b] <= wb
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.cu_wblk[mid] <= wb) lo = mid; else hi = mid;
   }
+  const int b = lo;
+  const int n_new = a.cu_rows[b + 1] - a.cu_rows[b];
+  const int blk_in_traj = wb - a.cu_wblk[b];
+  const int64_t row0 = a.cu_rows[b];
   const int first = a.first_pos[b];
   const int blk = first / 16 + blk_in_traj;                  // logical block
   const int t_lo = max(first, blk * 16), t_hi = min(first + n_new, blk * 16 + 16);
@@ -82,6 +73,30 @@ __device__ __forceinline__ void kv_write_block(const KvWriteLaunch& a, int wg) {
 }
 
 __global__ __launch_bounds__(256) void kv_write_kernel(KvWriteLaunch a) { kv_write_block(a, blockIdx.x); }
+
+// The row of a decode step: trajectory b stores row b of k / v at position first_pos[b].  One
+// workgroup per (trajectory, kv head).  The K row goes out as 16-byte pieces; the V row is one
+// 2-byte element per head-dim row of the transposed tile, stored as such (no read of the old
+// piece).  The row itself and the table offset are fetched before the position is known.
+__device__ __forceinline__ void kv_write_one_row(const KvWriteLaunch& a, int wg) {
+  const int b = wg / a.n_kv_heads;
+  const int h = wg - b * a.n_kv_heads;
+  const int D = a.head_dim;
+  const int tid = threadIdx.x;
+  const int64_t src = (static_cast<int64_t>(b) * a.n_kv_heads + h) * D;
+  u32x4 kpiece = {0u, 0u, 0u, 0u};
+  uint16_t vel = 0;
+  if (tid < D / 8) kpiece = *reinterpret_cast<const u32x4*>(a.k + src + tid * 8);
+  if (tid < D) vel = a.v[src + tid];
+  const int row_begin = a.row_off[b];
+  const int first = a.first_pos[b];
+  const int phys = a.block_ids[row_begin + first / 16];
+  const int slot = first % 16;
+  uint16_t* tile_k = a.pool + (static_cast<int64_t>(phys) * a.n_kv_heads + h) * 2 * 16 * D;
+  uint16_t* tile_v = tile_k + 16 * D;
+  if (tid < D / 8) *reinterpret_cast<u32x4*>(tile_k + slot * D + tid * 8) = kpiece;
+  if (tid < D) tile_v[tid * 16 + slot] = vel;
+}
 
 // Gathers whole blocks of the pool into a contiguous staging buffer (PACK) or scatters them
 // back under a list of physical blocks.  One workgroup moves one 4 KB slice of a block, one
@@ -130,7 +145,7 @@ __global__ __launch_bounds__(256) void plan_copy_rows_kernel(const u32x4* src, u
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i < n_vec) dst[i] = src[i];
   } else {
-    kv_write_block(a, static_cast<int>(blockIdx.x - copy_groups));
+    kv_write_one_row(a, static_cast<int>(blockIdx.x - copy_groups));
   }
 }
 
@@ -169,7 +184,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, uint
 
 hipError_t launch_kv_write(const KvWriteLaunch& a, hipStream_t stream) {
   if (a.n_rows <= 0 || a.n_wblk <= 0) return hipSuccess;
-  if (a.head_dim > 128) return hipErrorInvalidValue;
+  if (a.head_dim > 128 || a.one_row_each) return hipErrorInvalidValue;   // single rows go with the plan copy
   const dim3 grid(static_cast<unsigned>(a.n_wblk) * static_cast<unsigned>(a.n_kv_heads));
   hipLaunchKernelGGL(kv_write_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
